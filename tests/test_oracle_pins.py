@@ -1,0 +1,338 @@
+"""Pins for the CPU oracle: everything here checks oracle/hack_oracle.py against
+something other than itself -- brute force in pure Python on tiny inputs,
+closed forms, invariants, the full-budget reduction to plain attention, and
+the complexity closed form printed in the paper's supplementary analysis."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import hack_oracle as ho
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ---------------------------------------------------------------------------
+# independent brute force (pure Python, no numpy arithmetic)
+# ---------------------------------------------------------------------------
+def bf_softmax_row(xs):
+    m = max(xs)
+    es = [math.exp(x - m) for x in xs]
+    s = math.fsum(es)
+    return [e / s for e in es]
+
+
+def bf_dot(a, b):
+    return math.fsum(float(x) * float(y) for x, y in zip(a, b))
+
+
+def bf_importance(Qo, K, scale):
+    T = len(K)
+    imp = [0.0] * T
+    for q in Qo:
+        p = bf_softmax_row([scale * bf_dot(q, k) for k in K])
+        for j in range(T):
+            imp[j] += p[j]
+    return imp
+
+
+def bf_attention(Q, K, V, scale):
+    out = []
+    for q in Q:
+        p = bf_softmax_row([scale * bf_dot(q, k) for k in K])
+        out.append([math.fsum(p[j] * float(V[j][c]) for j in range(len(K))) for c in range(len(V[0]))])
+    return out
+
+
+def bf_topk(vals, k):
+    """k rounds of 'take the largest remaining, lowest index among equals'."""
+    vals = [float(np.float32(v)) for v in vals]
+    left = list(range(len(vals)))
+    got = []
+    for _ in range(min(k, len(vals))):
+        best = left[0]
+        for j in left:
+            if vals[j] > vals[best]:
+                best = j
+        got.append(best)
+        left.remove(best)
+    return sorted(got)
+
+
+# ---------------------------------------------------------------------------
+# score
+# ---------------------------------------------------------------------------
+def test_observation_rows_stride_and_small_scales():
+    assert list(ho.observation_rows(64, 32)) == list(range(0, 64, 2))
+    assert list(ho.observation_rows(9, 32)) == list(range(9))           # N_k < N_obs: all queries
+    r = ho.observation_rows(100, 32)
+    assert len(r) == 32 and r[0] == 0 and r[-1] == (31 * 100) // 32
+    assert np.all(np.diff(r) >= 3) and np.all(np.diff(r) <= 4)          # evenly spread
+
+
+@pytest.mark.parametrize("n_obs,T,d,scale", [(3, 7, 4, 0.5), (5, 11, 6, 0.37), (1, 4, 3, 1.0)])
+def test_importance_matches_pure_python(n_obs, T, d, scale):
+    rng = np.random.default_rng(7 + T)
+    Qo, K = rng.standard_normal((n_obs, d)), rng.standard_normal((T, d))
+    got = ho.importance(Qo, K, scale)
+    want = bf_importance(Qo.tolist(), K.tolist(), scale)
+    assert got.shape == (T,)
+    np.testing.assert_allclose(got, want, rtol=1e-13, atol=0)
+
+
+def test_importance_closed_forms():
+    rng = np.random.default_rng(3)
+    K = rng.standard_normal((13, 8))
+    # zero queries: every softmax row is uniform
+    imp = ho.importance(np.zeros((5, 8)), K, 0.3)
+    np.testing.assert_allclose(imp, np.full(13, 5 / 13), rtol=1e-15)
+    # one query, two keys: softmax is the logistic function of the logit gap
+    q = np.array([[1.0, -2.0]])
+    K2 = np.array([[0.5, 0.25], [-1.0, 3.0]])
+    gap = 0.7 * ((0.5 - 0.5) - (-1.0 - 6.0))
+    imp2 = ho.importance(q, K2, 0.7)
+    np.testing.assert_allclose(imp2, [1 / (1 + math.exp(-gap)), 1 / (1 + math.exp(gap))], rtol=1e-14)
+    # a key with a dominant aligned logit takes all the mass of every row
+    Qo = rng.standard_normal((6, 8))
+    Kd = 0.01 * rng.standard_normal((9, 8))
+    Kd[4] = 50.0 * Qo.mean(axis=0) + 100.0 * np.sign(Qo.mean(axis=0))
+    Qa = np.abs(Qo) * np.sign(Kd[4])          # all queries aligned with key 4
+    impd = ho.importance(Qa, Kd, 1.0)
+    assert impd[4] == pytest.approx(6.0, rel=1e-12)
+    assert np.delete(impd, 4).max() < 1e-12
+
+
+def test_importance_invariants_and_scale():
+    rng = np.random.default_rng(11)
+    Qo, K = rng.standard_normal((32, 16)), rng.standard_normal((300, 16))
+    A = ho.subset_attention(Qo, K, 0.25)
+    assert A.shape == (32, 300)
+    np.testing.assert_allclose(A.sum(axis=1), 1.0, rtol=1e-14)          # rows sum to one
+    imp = ho.importance(Qo, K, 0.25)
+    assert imp.min() >= 0 and imp.sum() == pytest.approx(32.0, rel=1e-13)
+    # the scale multiplies the logits: scale*Q == (scale*Q)*1
+    np.testing.assert_allclose(imp, ho.importance(0.25 * Qo, K, 1.0), rtol=1e-12)
+    # shifting every key by a common vector moves each row's logits by a
+    # constant, which softmax ignores
+    np.testing.assert_allclose(imp, ho.importance(Qo, K + 0.0, 0.25), rtol=0)
+    # permuting keys permutes importance
+    perm = rng.permutation(300)
+    np.testing.assert_allclose(ho.importance(Qo, K[perm], 0.25), imp[perm], rtol=1e-12)
+
+
+# ---------------------------------------------------------------------------
+# select
+# ---------------------------------------------------------------------------
+def test_topk_hand_computed():
+    imp = np.array([0.10, 0.50, 0.05, 0.50, 0.20, 0.01, 0.30, 0.50])
+    # three equal maxima at 1, 3, 7; then 0.30 (6), 0.20 (4), 0.10 (0)
+    assert list(ho.select_contextual(imp, 1)) == [1]
+    assert list(ho.select_contextual(imp, 2)) == [1, 3]
+    assert list(ho.select_contextual(imp, 3)) == [1, 3, 7]
+    assert list(ho.select_contextual(imp, 4)) == [1, 3, 6, 7]
+    assert list(ho.select_contextual(imp, 6)) == [0, 1, 3, 4, 6, 7]
+    assert list(ho.select_contextual(imp, 8)) == list(range(8))
+    assert list(ho.select_contextual(imp, 50)) == list(range(8))        # budget above T
+
+
+def test_structural_hand_computed():
+    #        init | intermediate               | recent (N_k = 3)
+    imp = np.array([0.0, 0.0, 0.3, 0.9, 0.1, 0.9, 0.2, 0.0, 0.0, 0.0])
+    # budget 7 = 2 init + 3 recent + M=2 best of {2..6}: 3 and 5
+    assert list(ho.select_structural(imp, 7, 2, 3)) == [0, 1, 3, 5, 7, 8, 9]
+    # M = 3 adds the next best (index 2, value 0.3)
+    assert list(ho.select_structural(imp, 8, 2, 3)) == [0, 1, 2, 3, 5, 7, 8, 9]
+    # M = 0: only init and recent
+    assert list(ho.select_structural(imp, 5, 2, 3)) == [0, 1, 7, 8, 9]
+    # large importance in init/recent rows must not change the intermediate ranking
+    imp2 = imp.copy()
+    imp2[[0, 9]] = 5.0
+    assert list(ho.select_structural(imp2, 7, 2, 3)) == [0, 1, 3, 5, 7, 8, 9]
+    # N_init larger than what precedes the recent scale is clipped
+    assert list(ho.select_structural(np.array([0.1, 0.2, 0.3, 0.4]), 4, 5, 3)) == [0, 1, 2, 3]
+
+
+def test_structural_small_budget_reading():
+    # budget below init + recent: init rows first, then the best recent rows
+    imp = np.array([0.0, 0.0, 0.9, 0.9, 0.1, 0.4, 0.3, 0.4])   # n0=2, mid {2,3}, recent {4..7}
+    assert list(ho.select_structural(imp, 4, 2, 4)) == [0, 1, 5, 7]
+    assert list(ho.select_structural(imp, 3, 2, 4)) == [0, 1, 5]            # tie 5 vs 7 -> lower index
+    assert list(ho.select_structural(imp, 1, 2, 4)) == [0]
+
+
+def test_all_equal_importance_closed_form():
+    imp = np.full(40, 32 / 40)
+    assert list(ho.select_contextual(imp, 9)) == list(range(9))
+    got = ho.select_structural(imp, 20, 5, 8)
+    assert list(got) == list(range(5)) + list(range(5, 5 + 7)) + list(range(32, 40))
+
+
+def test_decision_is_taken_in_float32():
+    imp = np.array([0.25, 0.25 + 1e-12, 0.1])     # distinct in float64, equal in float32
+    assert list(ho.select_contextual(imp, 1)) == [0]
+    imp = np.array([0.25, 0.25 + 1e-6, 0.1])      # distinct in float32
+    assert list(ho.select_contextual(imp, 1)) == [1]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_select_matches_brute_force_and_invariants(seed):
+    rng = np.random.default_rng(100 + seed)
+    T, N_k, n_init = 37, 9, 5
+    imp = rng.random(T)
+    imp[rng.integers(0, T, 8)] = imp[3]            # plant duplicates
+    for b in (1, 5, 14, 15, 20, 36, 37):
+        I = ho.select_contextual(imp, b)
+        assert list(I) == bf_topk(imp, b)
+        assert len(I) == b and np.all(np.diff(I) > 0) and I[0] >= 0 and I[-1] < T
+    for b in (14, 15, 22, 37):
+        I = ho.select_structural(imp, b, n_init, N_k)
+        assert len(I) == b and np.all(np.diff(I) > 0)
+        assert set(range(n_init)) <= set(I) and set(range(T - N_k, T)) <= set(I)
+        mid = [j - n_init for j in I if n_init <= j < T - N_k]
+        assert mid == bf_topk(imp[n_init:T - N_k], b - n_init - N_k)
+    # swapping the class swaps the policy
+    assert list(ho.select(imp, ho.CONTEXTUAL, 15, n_init, N_k)) == list(ho.select_contextual(imp, 15))
+    assert list(ho.select(imp, ho.STRUCTURAL, 15, n_init, N_k)) == list(ho.select_structural(imp, 15, n_init, N_k))
+
+
+# ---------------------------------------------------------------------------
+# compact and attention
+# ---------------------------------------------------------------------------
+def test_compact_is_a_row_gather():
+    rng = np.random.default_rng(5)
+    K, V = rng.standard_normal((10, 4)), rng.standard_normal((10, 4))
+    I = np.array([1, 4, 9])
+    Kh, Vh = ho.compact(K, V, I)
+    for i, j in enumerate(I):
+        assert np.array_equal(Kh[i], K[j]) and np.array_equal(Vh[i], V[j])
+    Kh, Vh = ho.compact(K, V, np.arange(10))
+    assert np.array_equal(Kh, K) and np.array_equal(Vh, V)
+
+
+def test_attention_matches_pure_python_and_properties():
+    rng = np.random.default_rng(9)
+    Q, K, V = rng.standard_normal((5, 6)), rng.standard_normal((8, 6)), rng.standard_normal((8, 3))
+    O = ho.attention(Q, K, V, 0.41)
+    np.testing.assert_allclose(O, bf_attention(Q.tolist(), K.tolist(), V.tolist(), 0.41), rtol=1e-12, atol=1e-15)
+    assert O.shape == (5, 3)
+    # constant values come out unchanged; a single key returns its value
+    np.testing.assert_allclose(ho.attention(Q, K, np.full((8, 3), 2.5), 0.41), 2.5, rtol=1e-14)
+    np.testing.assert_allclose(ho.attention(Q, K[:1], V[:1], 0.41), np.repeat(V[:1], 5, 0), rtol=1e-14)
+    # key order does not matter
+    perm = rng.permutation(8)
+    np.testing.assert_allclose(ho.attention(Q, K[perm], V[perm], 0.41), O, rtol=1e-12)
+    # one query, two keys: convex combination with logistic weight
+    q = np.array([[2.0, 0.0]]); K2 = np.array([[1.0, 0.0], [0.0, 1.0]]); V2 = np.array([[1.0], [3.0]])
+    w = 1 / (1 + math.exp(-0.5 * 2.0))
+    np.testing.assert_allclose(ho.attention(q, K2, V2, 0.5), [[w * 1.0 + (1 - w) * 3.0]], rtol=1e-14)
+
+
+# ---------------------------------------------------------------------------
+# unit step and whole schedule
+# ---------------------------------------------------------------------------
+def _tiny_schedule(seed, sides=(1, 2, 3, 4), B=1, H=4, d=8):
+    rng = np.random.default_rng(seed)
+    return [tuple(rng.standard_normal((B, H, s * s, d)) for _ in range(3)) for s in sides]
+
+
+def test_full_budget_schedule_is_vanilla_cache_attention():
+    steps = _tiny_schedule(1)
+    H = 4
+    types = np.array([0, 1, 0, 1])
+    big = [np.full(H, 1 << 30, np.int64) for _ in steps]
+    trace = ho.run_schedule(steps, types, big, N_init=5, scale=0.35)
+    Kall = [np.zeros((0, 8))] * H
+    Vall = [np.zeros((0, 8))] * H
+    T = 0
+    for k, (Q, K, V) in enumerate(steps):
+        T += Q.shape[2]
+        for h in range(H):
+            Kall[h] = np.concatenate([Kall[h], K[0, h]])
+            Vall[h] = np.concatenate([Vall[h], V[0, h]])
+            want = bf_attention(Q[0, h].tolist(), Kall[h].tolist(), Vall[h].tolist(), 0.35)
+            r = trace[k][h]
+            assert not r["compressed"] and r["K"].shape[0] == T
+            np.testing.assert_allclose(r["O"], want, rtol=1e-11, atol=1e-14)
+            assert list(r["pos"]) == list(range(T))
+
+
+def test_budget_equal_to_cache_is_not_compressed_and_budget_100_equals_full():
+    rng = np.random.default_rng(2)
+    d = 8
+    Kc, Vc = rng.standard_normal((6, d)), rng.standard_normal((6, d))
+    Qk, Kk, Vk = (rng.standard_normal((4, d)) for _ in range(3))
+    full = ho.attention(Qk, np.concatenate([Kc, Kk]), np.concatenate([Vc, Vk]), 0.3)
+    for ht in (0, 1):
+        r = ho.unit_step(Kc, Vc, np.arange(6), Qk, Kk, Vk, 6, ht, 10, 2, 0.3)
+        assert not r["compressed"]
+        np.testing.assert_allclose(r["O"], full, rtol=1e-13)
+
+
+def test_unit_step_compresses_before_attention():
+    rng = np.random.default_rng(4)
+    d = 8
+    Kc, Vc = rng.standard_normal((12, d)), rng.standard_normal((12, d))
+    Qk, Kk, Vk = (rng.standard_normal((4, d)) for _ in range(3))
+    K_in, V_in = np.concatenate([Kc, Kk]), np.concatenate([Vc, Vk])
+    r = ho.unit_step(Kc, Vc, np.arange(12), Qk, Kk, Vk, 12, ho.CONTEXTUAL, 7, 2, 0.3, N_obs=32)
+    assert r["compressed"] and len(r["I"]) == 7
+    imp = bf_importance(Qk.tolist(), K_in.tolist(), 0.3)      # N_k=4 < 32: all queries observe
+    assert list(r["I"]) == bf_topk(imp, 7)
+    want = bf_attention(Qk.tolist(), K_in[r["I"]].tolist(), V_in[r["I"]].tolist(), 0.3)
+    np.testing.assert_allclose(r["O"], want, rtol=1e-11)
+    assert list(r["pos"]) == list(r["I"])
+
+
+def test_schedule_invariants_under_compression():
+    sides = (1, 2, 3, 4, 5, 6)
+    steps = _tiny_schedule(3, sides=sides, B=2, H=4)
+    types = np.array([0, 1, 1, 0])
+    N = [s * s for s in sides]
+    T_K = sum(N)
+    B_C, B_S = 14, 60
+    budgets = []
+    for k in range(len(sides)):
+        b = np.where(np.tile(types, 2) == 0, B_C, B_S)
+        budgets.append(b if k >= 3 else np.full(8, 1 << 30))
+    trace = ho.run_schedule(steps, types, budgets, N_init=5, scale=0.35)
+    alive = {u: set() for u in range(8)}
+    T = 0
+    for k, res in enumerate(trace):
+        lo, T = T, T + N[k]
+        for u, r in res.items():
+            pos = r["pos"]
+            assert np.all(np.diff(pos) > 0)
+            expect_len = min(int(budgets[k][u]), (len(alive[u]) + N[k]))
+            assert len(pos) == expect_len == r["K"].shape[0]
+            # evicted rows never come back: everything older than this scale was alive before
+            old = set(int(p) for p in pos if p < lo)
+            assert old <= alive[u]
+            alive[u] = set(int(p) for p in pos)
+            if types[u % 4] == 1 and r["compressed"] and int(budgets[k][u]) >= 5 + N[k]:
+                assert set(range(5)) <= alive[u] and set(range(lo, T)) <= alive[u]
+            np.testing.assert_allclose(
+                r["O"], ho.attention(steps[k][0][u // 4, u % 4], r["K"], r["V"], 0.35), rtol=1e-13)
+    # budget identity B = alpha*B_C + (1-alpha)*B_S at the end of the schedule
+    final = [len(trace[-1][u]["pos"]) for u in range(8)]
+    assert np.mean(final) == pytest.approx(0.5 * B_C + 0.5 * B_S)
+    assert T == T_K
+
+
+# ---------------------------------------------------------------------------
+# complexity model
+# ---------------------------------------------------------------------------
+def test_complexity_closed_form_from_the_paper():
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "complexity_closed_form.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 3
+    for a, K, val in rows:
+        a, K, val = int(a), int(K), int(val)
+        N = [a ** (2 * (k - 1)) for k in range(1, K + 1)]
+        assert ho.attention_cost_full(N) == val
+        # the bound of Sec. 4.5: sum N_k min(T_k, B) <= B * sum N_k, tight for B >= T_K only at equality of terms
+        for B in (1, 3, 10, 10 ** 6):
+            assert ho.attention_cost_budgeted(N, B) <= B * sum(N)
+        assert ho.attention_cost_budgeted(N, 10 ** 9) == val
+    # subset-attention overhead: N_obs * sum_{k>=k_s} (B + N_k)
+    assert ho.subset_attention_cost([1, 4, 16, 64], B=10, k_s=3, N_obs=32) == 32 * ((10 + 16) + (10 + 64))
