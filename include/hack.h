@@ -1,0 +1,199 @@
+/*
+ * hack.h -- C ABI of the MI355X (gfx950) library for head-aware KV-cache
+ * compression in next-scale visual autoregressive generation
+ * (arXiv 2504.09261).
+ *
+ * One "unit" is one (batch, head) pair, u = b*H + h.  At every scale step each
+ * unit (i) scores its cache against a few of the current scale's queries,
+ * (ii) selects a budget-limited subset under its head class's policy,
+ * (iii) compacts the kept K/V rows, and (iv) lets the current scale's queries
+ * attend over the compacted cache.  Units are independent.
+ *
+ * Conventions
+ *  - Every call returns a hack_status (0 = OK, negative = error).  No C++
+ *    exception crosses the ABI; hack_last_error() gives the message.
+ *  - Pointers marked DEVICE point to GPU memory owned by the caller; pointers
+ *    marked HOST are ordinary host arrays, read (or written) during the call
+ *    and not retained.
+ *  - Calls are asynchronous on the given HIP stream (a hipStream_t passed as
+ *    void*).  They never synchronise the device and never read device memory
+ *    from the host: every length is host-computable (len_out = min(budget, T_in)).
+ *  - Element type and head_dim are fixed per context.  Tensors are row-major;
+ *    a cache row is head_dim elements.  q/k_new/v_new/out are [B, H, N_k, head_dim].
+ *  - Arguments are validated on the host before anything is launched; on error
+ *    nothing has been launched.
+ *  - A context serves one stream at a time (its workspace is shared by calls).
+ *  - Small per-call launch tables (offsets, lengths, work lists) are uploaded
+ *    the first time a particular table is seen and reused afterwards, so a
+ *    repeated schedule issues kernel launches only and can be captured in a
+ *    HIP graph after one eager warm-up pass.
+ */
+#ifndef HACK_MI355X_H
+#define HACK_MI355X_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hack_ctx hack_ctx;
+typedef struct hack_kvcache hack_kvcache;
+typedef void* hack_stream; /* hipStream_t */
+
+typedef enum {
+  HACK_OK = 0,
+  HACK_EINVAL = -1,       /* bad argument (shape, range, alignment, NULL) */
+  HACK_ECAPACITY = -2,    /* exceeds what the context / cache was sized for */
+  HACK_EUNSUPPORTED = -3, /* valid request this build does not implement */
+  HACK_EHIP = -4          /* a HIP runtime call failed */
+} hack_status;
+
+typedef enum { HACK_BF16 = 0, HACK_F32 = 1 } hack_dtype;
+
+enum { HACK_CONTEXTUAL = 0, HACK_STRUCTURAL = 1 };
+
+typedef struct {
+  int32_t device;        /* HIP device ordinal */
+  int32_t heads;         /* H */
+  int32_t head_dim;      /* 64 or 128 */
+  int32_t dtype;         /* hack_dtype of q/k/v/out and of the cache */
+  int32_t max_units;     /* largest B*H of any call */
+  int32_t max_cache_len; /* largest T_in (cache rows + current scale) of any unit */
+  int32_t max_queries;   /* largest N_k */
+  int32_t n_obs;         /* observation queries N_obs, 1..32 (paper: 32) */
+} hack_config;
+
+/* Ragged per-unit cache: rows of unit u are [off[u], off[u] + len[u]) of k and v. */
+typedef struct {
+  void* k;            /* DEVICE [rows, head_dim] */
+  void* v;            /* DEVICE [rows, head_dim] */
+  int32_t* pos;       /* DEVICE [rows] global token id of every row, or NULL */
+  int64_t rows;       /* rows allocated in k, v (and pos) */
+  const int64_t* off; /* HOST [B*H] first row of each unit; multiples of 8 */
+  const int32_t* len; /* HOST [B*H] valid rows of each unit */
+} hack_cache;
+
+/* ---- life cycle ------------------------------------------------------- */
+
+/* Creates a context on cfg->device and allocates its workspace (importance,
+ * kept indices, softmax partials, launch tables).  Returns HACK_EINVAL for an
+ * unsupported head_dim/dtype/n_obs or non-positive sizes, HACK_EHIP if the
+ * device cannot be used. */
+hack_status hack_create(hack_ctx** out, const hack_config* cfg);
+void hack_destroy(hack_ctx* ctx);
+const char* hack_strerror(hack_status s);
+/* Message of the last failing call on ctx (valid until the next call). */
+const char* hack_last_error(const hack_ctx* ctx);
+
+/* ---- a1: importance estimation by subset attention --------------------
+ * Sec. 4.4, "Importance Estimation via Efficient Subset Attention":
+ *   A~ = Softmax(scale * Q~ K^T) over the uncompressed keys of this step,
+ *   importance[j] = sum_i A~[i, j].
+ * The keys of unit u are its cache rows followed, if k_new != NULL, by the
+ * N_k rows k_new[b, h] (the concatenation of the cache-update equation,
+ * without materialising it): T_in[u] = in->len[u] + (k_new ? N_k : 0).
+ *   q        DEVICE [B, H, N_k, d]
+ *   q_idx    HOST [n_obs] rows of q that observe, or NULL for the evenly
+ *            strided rows floor(i*N_k/n_obs); n_obs <= min(ctx n_obs, N_k)
+ *   active   HOST [B*H] nonzero = score this unit, or NULL = all units
+ *   importance DEVICE float [B*H, imp_stride]; row u receives T_in[u] values
+ *            (rows of inactive units are left untouched)
+ * Errors: HACK_EINVAL (NULL/misaligned pointers, n_obs out of range, a q_idx
+ * outside [0, N_k), offsets outside the cache), HACK_ECAPACITY (B*H, N_k or a
+ * T_in above the context's limits, imp_stride < max T_in). */
+hack_status hack_score(hack_ctx* ctx, int32_t B, int32_t N_k, const void* q,
+                       const int32_t* q_idx, int32_t n_obs, float scale,
+                       const hack_cache* in, const void* k_new,
+                       const uint8_t* active, float* importance,
+                       int64_t imp_stride, hack_stream stream);
+
+/* ---- a2: budgeted selection per head class -----------------------------
+ * Sec. 4.4, f_C and f_S.  For unit u with T = t_in[u], b = min(budget[u], T):
+ *   contextual: the b keys of largest importance;
+ *   structural: the first n0 = min(n_init, T - n_recent) rows, the last
+ *     n_recent rows, and the M = b - n0 - n_recent most important rows in
+ *     between; if M < 0, the first min(n0, b) rows and the most important
+ *     rows of the last n_recent.
+ * Equal importance is resolved towards the lower index; indices are written
+ * in ascending order.  Importance is compared as float32 bit patterns of
+ * non-negative, non-NaN numbers.
+ *   importance DEVICE float [B*H, imp_stride]
+ *   head_type  HOST [H], HACK_CONTEXTUAL / HACK_STRUCTURAL
+ *   kept_idx   DEVICE int32 [B*H, idx_stride]; row u receives b indices
+ *   len_out    HOST [B*H] receives b (may be NULL)
+ * budget[u] >= T writes the identity selection 0..T-1.
+ * Errors: HACK_EINVAL (budget < 1, n_recent > T, bad head_type),
+ * HACK_ECAPACITY (T above the context's max_cache_len, strides too small). */
+hack_status hack_select(hack_ctx* ctx, int32_t B, const float* importance,
+                        int64_t imp_stride, const int32_t* t_in,
+                        const uint8_t* head_type, const int32_t* budget,
+                        int32_t n_init, int32_t n_recent, int32_t* kept_idx,
+                        int64_t idx_stride, int32_t* len_out,
+                        hack_stream stream);
+
+/* ---- a3: compaction ------------------------------------------------------
+ * Sec. 4.4: K^ = K[I, :], V^ = V[I, :].  Row i of unit u in `out` becomes row
+ * kept_idx[u, i] of the virtual concatenation (in rows, then k_new/v_new rows)
+ * for i < out->len[u].  Bit-exact copy.  `pos` is gathered too when both
+ * caches carry it (rows from k_new get pos_new + their row number).  `out` must
+ * not overlap the rows of `in` that are read.
+ * Errors: HACK_EINVAL (NULL, overlapping ranges, out rows outside out->rows). */
+hack_status hack_compact(hack_ctx* ctx, int32_t B, int32_t N_k,
+                         const hack_cache* in, const void* k_new,
+                         const void* v_new, int32_t pos_new,
+                         const int32_t* kept_idx, int64_t idx_stride,
+                         const hack_cache* out, hack_stream stream);
+
+/* ---- a4: attention of the current scale over the ragged cache -----------
+ * Preliminaries, attention equation: O = Softmax(scale * Q K^T) V for every
+ * unit over its own kv->len[u] rows, no mask.  out has the layout and element
+ * type of q.  Every unit must have at least one row.
+ * Errors: HACK_EINVAL, HACK_ECAPACITY as above. */
+hack_status hack_attn(hack_ctx* ctx, int32_t B, int32_t N_k, const void* q,
+                      const hack_cache* kv, float scale, void* out,
+                      hack_stream stream);
+
+/* ---- a5: the whole step on a library-managed cache -----------------------
+ * The managed cache gives every unit two slabs of cap[u] rows inside memory
+ * the caller provides (compaction writes from one slab to the other; a unit
+ * that does not compress appends in place).  cap[u] must cover the longest
+ * cache the unit ever holds after a step (normally its budget).
+ *
+ * hack_kvcache_rows_required: rows k_mem/v_mem/pos_mem must hold. */
+hack_status hack_kvcache_rows_required(int32_t n_units, const int32_t* cap,
+                                       int64_t* rows);
+/* k_mem, v_mem: DEVICE [mem_rows, head_dim]; pos_mem: DEVICE int32 [mem_rows] or NULL. */
+hack_status hack_kvcache_create(hack_ctx* ctx, int32_t n_units,
+                                const int32_t* cap, void* k_mem, void* v_mem,
+                                int32_t* pos_mem, int64_t mem_rows,
+                                hack_kvcache** out);
+void hack_kvcache_destroy(hack_kvcache* c);
+/* Forget all rows (start of a new image). */
+hack_status hack_kvcache_reset(hack_kvcache* c);
+/* Current state as a hack_cache; view->off/len point into c and stay valid
+ * until the next hack_step / reset / destroy on c. */
+hack_status hack_kvcache_view(const hack_kvcache* c, hack_cache* view);
+
+/* One scale step for all units of a layer (Sec. 4.3: compression is applied
+ * prior to the attention computation whenever a unit's cache exceeds its
+ * budget): append k_new/v_new, and for every unit with budget[u] < T_in[u]
+ * score -> select -> compact; then attention over the resulting cache.
+ * Observation rows are the evenly strided n_obs = min(cfg n_obs, N_k).
+ *   head_type HOST [H]; budget HOST [B*H]; n_init as in hack_select
+ *   out DEVICE [B, H, N_k, d]
+ *   kept_idx_opt DEVICE int32 [B*H, idx_stride] or NULL: receives the kept
+ *     indices of compressing units (rows of other units untouched).
+ * Errors: as the individual calls; HACK_ECAPACITY if a unit would outgrow its slab. */
+hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B,
+                      int32_t N_k, const void* q, const void* k_new,
+                      const void* v_new, const uint8_t* head_type,
+                      const int32_t* budget, int32_t n_init, float scale,
+                      void* out, int32_t* kept_idx_opt, int64_t idx_stride,
+                      hack_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HACK_MI355X_H */

@@ -1,0 +1,608 @@
+// Host side of the C ABI declared in include/hack.h: argument validation, the
+// host planner that turns (head class, budget, N_init, N_k) into per-unit launch
+// tables, the launch-table cache, the managed double-slab cache of hack_step,
+// and the kernel launches.  No device memory is ever read from the host.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <unordered_map>
+#include <vector>
+
+#include "../../include/hack.h"
+#include "hack_internal.h"
+
+using namespace hack;
+
+// ---------------------------------------------------------------------------
+// context
+// ---------------------------------------------------------------------------
+namespace {
+
+constexpr size_t kArenaBytes = 32u << 20;  // launch tables (device + pinned mirror)
+constexpr size_t kAlign = 256;
+
+struct TableEntry {
+  size_t offset;  // into both arenas
+  size_t bytes;
+};
+
+}  // namespace
+
+struct hack_ctx {
+  hack_config cfg;
+  int elem_bytes = 2;
+  // workspace
+  float* importance = nullptr;   // [max_units, ws_stride]
+  int32_t* kept = nullptr;       // [max_units, ws_stride]
+  double* stats = nullptr;       // [max_units, max_chunks, 32, 2]
+  int64_t ws_stride = 0;
+  int max_chunks = 0;
+  // launch-table cache
+  uint8_t* arena_dev = nullptr;
+  uint8_t* arena_host = nullptr;  // pinned
+  size_t arena_used = 0;
+  std::unordered_multimap<uint64_t, TableEntry> tables;
+  std::string err;
+};
+
+struct hack_kvcache {
+  hack_ctx* ctx;
+  int32_t n_units;
+  std::vector<int32_t> cap;
+  std::vector<int64_t> slab[2];
+  std::vector<uint8_t> cur;
+  std::vector<int64_t> off;
+  std::vector<int32_t> len;
+  void* k;
+  void* v;
+  int32_t* pos;
+  int64_t rows;
+  int64_t tokens_seen;
+};
+
+namespace {
+
+hack_status fail(hack_ctx* ctx, hack_status s, const char* fmt, ...) {
+  if (ctx) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    ctx->err = buf;
+  }
+  return s;
+}
+
+#define HIP_TRY(ctx, call)                                                              \
+  do {                                                                                  \
+    hipError_t e_ = (call);                                                             \
+    if (e_ != hipSuccess)                                                               \
+      return fail(ctx, HACK_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));      \
+  } while (0)
+
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+uint64_t fnv1a(const uint8_t* p, size_t n) {
+  uint64_t h = 1469598103934665603ull;
+  for (size_t i = 0; i < n; ++i) {
+    h ^= p[i];
+    h *= 1099511628211ull;
+  }
+  return h;
+}
+
+// A launch table under construction: sections are appended 64-byte aligned.
+struct Table {
+  std::vector<uint8_t> bytes;
+  template <typename T>
+  size_t add(const T* data, size_t count) {
+    const size_t off = (bytes.size() + 63) / 64 * 64;
+    bytes.resize(off + std::max<size_t>(count, 1) * sizeof(T), 0);
+    if (count) memcpy(bytes.data() + off, data, count * sizeof(T));
+    return off;
+  }
+};
+
+// Returns the device address of a table with these contents, uploading it on
+// the given stream the first time it is seen.  Entries are immutable; both
+// copies live until the context is destroyed (or the arena is recycled).
+hack_status table_device(hack_ctx* ctx, const Table& t, hipStream_t stream, const uint8_t** dev) {
+  const size_t n = t.bytes.size();
+  const uint64_t h = fnv1a(t.bytes.data(), n);
+  auto range = ctx->tables.equal_range(h);
+  for (auto it = range.first; it != range.second; ++it) {
+    if (it->second.bytes == n && memcmp(ctx->arena_host + it->second.offset, t.bytes.data(), n) == 0) {
+      *dev = ctx->arena_dev + it->second.offset;
+      return HACK_OK;
+    }
+  }
+  const size_t need = (size_t)round_up((int64_t)n, kAlign);
+  if (need > kArenaBytes) return fail(ctx, HACK_ECAPACITY, "launch table of %zu bytes exceeds the arena", n);
+  if (ctx->arena_used + need > kArenaBytes) {
+    // Recycle: every table may still be referenced by queued work, so drain first.
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    (void)hipStreamIsCapturing(stream, &cs);
+    if (cs != hipStreamCaptureStatusNone)
+      return fail(ctx, HACK_ECAPACITY, "launch-table arena full during stream capture");
+    HIP_TRY(ctx, hipDeviceSynchronize());
+    ctx->tables.clear();
+    ctx->arena_used = 0;
+  }
+  const size_t off = ctx->arena_used;
+  memcpy(ctx->arena_host + off, t.bytes.data(), n);
+  HIP_TRY(ctx, hipMemcpyAsync(ctx->arena_dev + off, ctx->arena_host + off, n, hipMemcpyHostToDevice, stream));
+  ctx->arena_used += need;
+  ctx->tables.emplace(h, TableEntry{off, n});
+  *dev = ctx->arena_dev + off;
+  return HACK_OK;
+}
+
+// Sec. 4.4 policies as index ranges (see hack_select in hack.h).
+void plan_select(int type, int T, int b, int n_init, int n_recent, UnitDesc* d) {
+  if (b >= T) {  // identity
+    d->keep_a = T; d->sel_lo = T; d->sel_hi = T; d->sel_m = 0; d->keep_b = T;
+    return;
+  }
+  if (type == HACK_CONTEXTUAL) {
+    d->keep_a = 0; d->sel_lo = 0; d->sel_hi = T; d->sel_m = b; d->keep_b = T;
+    return;
+  }
+  const int n_rec = std::min(n_recent, T);
+  const int n0 = std::max(0, std::min(n_init, T - n_rec));
+  const int M = b - n0 - n_rec;
+  if (M >= 0) {
+    d->keep_a = n0; d->sel_lo = n0; d->sel_hi = T - n_rec; d->sel_m = M; d->keep_b = T - n_rec;
+  } else {  // budget below init + recent: init rows, then the best of the recent scale
+    const int ka = std::min(n0, b);
+    d->keep_a = ka; d->sel_lo = T - n_rec; d->sel_hi = T; d->sel_m = b - ka; d->keep_b = T;
+  }
+}
+
+hack_status check_common(hack_ctx* ctx, int32_t B, int32_t N_k, bool need_nk) {
+  if (!ctx) return HACK_EINVAL;
+  if (B < 1) return fail(ctx, HACK_EINVAL, "B must be >= 1 (got %d)", B);
+  if ((int64_t)B * ctx->cfg.heads > ctx->cfg.max_units)
+    return fail(ctx, HACK_ECAPACITY, "B*H = %lld exceeds max_units %d", (long long)B * ctx->cfg.heads, ctx->cfg.max_units);
+  if (need_nk) {
+    if (N_k < 1) return fail(ctx, HACK_EINVAL, "N_k must be >= 1 (got %d)", N_k);
+    if (N_k > ctx->cfg.max_queries) return fail(ctx, HACK_ECAPACITY, "N_k = %d exceeds max_queries %d", N_k, ctx->cfg.max_queries);
+  }
+  return HACK_OK;
+}
+
+hack_status check_cache(hack_ctx* ctx, const hack_cache* c, int n_units, const char* name, bool need_v) {
+  if (!c) return fail(ctx, HACK_EINVAL, "%s is NULL", name);
+  if (!c->k || (need_v && !c->v) || !c->off || !c->len) return fail(ctx, HACK_EINVAL, "%s has a NULL member", name);
+  if (!aligned16(c->k) || (c->v && !aligned16(c->v))) return fail(ctx, HACK_EINVAL, "%s k/v must be 16-byte aligned", name);
+  if (c->rows < 0) return fail(ctx, HACK_EINVAL, "%s rows < 0", name);
+  for (int u = 0; u < n_units; ++u) {
+    if (c->len[u] < 0 || c->off[u] < 0 || (c->off[u] & 7) || c->off[u] + c->len[u] > c->rows)
+      return fail(ctx, HACK_EINVAL, "%s unit %d: off %lld len %d outside [0, %lld) or off not a multiple of 8", name, u,
+                  (long long)c->off[u], c->len[u], (long long)c->rows);
+  }
+  return HACK_OK;
+}
+
+bool scale_ok(float s) { return std::isfinite(s) && s > 0.f; }
+
+// Attention work items: units dealt to the 8 XCDs in order of decreasing length
+// (work-group ids are dispatched round-robin over XCDs, so id%8 picks the XCD);
+// within an XCD all tiles of a unit are adjacent, so its K/V stay in that XCD's L2.
+void build_attn_items(const std::vector<UnitDesc>& descs, int N_k, int tile_rows, std::vector<AttnItem>* items) {
+  const int n = (int)descs.size();
+  std::vector<int> order(n);
+  for (int i = 0; i < n; ++i) order[i] = i;
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return descs[a].n_out > descs[b].n_out; });
+  const int tiles = (N_k + tile_rows - 1) / tile_rows;
+  constexpr int X = 8;
+  std::vector<AttnItem> per[X];
+  int64_t load[X] = {0};
+  for (int r = 0; r < n; ++r) {
+    int x = 0;
+    for (int i = 1; i < X; ++i) if (load[i] < load[x]) x = i;   // least-loaded XCD
+    load[x] += (int64_t)descs[order[r]].n_out * tiles;
+    for (int t = 0; t < tiles; ++t) per[x].push_back(AttnItem{order[r], t});
+  }
+  size_t longest = 0;
+  for (int x = 0; x < X; ++x) longest = std::max(longest, per[x].size());
+  items->assign(longest * X, AttnItem{-1, 0});
+  for (int x = 0; x < X; ++x)
+    for (size_t i = 0; i < per[x].size(); ++i) (*items)[i * X + x] = per[x][i];
+}
+
+void fill_q_rows(const int32_t* q_idx, int n_obs, int N_k, int32_t* rows) {
+  for (int i = 0; i < kMaxObs; ++i) rows[i] = 0;
+  for (int i = 0; i < n_obs; ++i) rows[i] = q_idx ? q_idx[i] : (int32_t)(((int64_t)i * N_k) / n_obs);
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// life cycle
+// ---------------------------------------------------------------------------
+extern "C" const char* hack_strerror(hack_status s) {
+  switch (s) {
+    case HACK_OK: return "ok";
+    case HACK_EINVAL: return "invalid argument";
+    case HACK_ECAPACITY: return "capacity exceeded";
+    case HACK_EUNSUPPORTED: return "unsupported";
+    case HACK_EHIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+extern "C" const char* hack_last_error(const hack_ctx* ctx) { return ctx ? ctx->err.c_str() : "NULL context"; }
+
+extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
+  if (!out || !cfg) return HACK_EINVAL;
+  *out = nullptr;
+  if (cfg->head_dim != 64 && cfg->head_dim != 128) return HACK_EINVAL;
+  if (cfg->dtype != HACK_BF16 && cfg->dtype != HACK_F32) return HACK_EINVAL;
+  if (cfg->heads < 1 || cfg->max_units < cfg->heads || cfg->max_cache_len < 1 || cfg->max_queries < 1) return HACK_EINVAL;
+  if (cfg->n_obs < 1 || cfg->n_obs > kMaxObs) return HACK_EINVAL;
+  if (cfg->max_cache_len > 32768) return HACK_EUNSUPPORTED;  // selection keeps a unit's keys in LDS
+  hack_ctx* ctx = new (std::nothrow) hack_ctx();
+  if (!ctx) return HACK_EHIP;
+  ctx->cfg = *cfg;
+  ctx->elem_bytes = cfg->dtype == HACK_F32 ? 4 : 2;
+  ctx->ws_stride = round_up(cfg->max_cache_len, 64);
+  ctx->max_chunks = (cfg->max_cache_len + kScoreChunk - 1) / kScoreChunk;
+  hipError_t e = hipSetDevice(cfg->device);
+  const size_t n_ws = (size_t)cfg->max_units * ctx->ws_stride;
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->importance, n_ws * sizeof(float));
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->kept, n_ws * sizeof(int32_t));
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->stats, (size_t)cfg->max_units * ctx->max_chunks * kMaxObs * 2 * sizeof(double));
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->arena_dev, kArenaBytes);
+  if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->arena_host, kArenaBytes, hipHostMallocDefault);
+  if (e != hipSuccess) {
+    hack_destroy(ctx);
+    return HACK_EHIP;
+  }
+  *out = ctx;
+  return HACK_OK;
+}
+
+extern "C" void hack_destroy(hack_ctx* ctx) {
+  if (!ctx) return;
+  if (ctx->importance) (void)hipFree(ctx->importance);
+  if (ctx->kept) (void)hipFree(ctx->kept);
+  if (ctx->stats) (void)hipFree(ctx->stats);
+  if (ctx->arena_dev) (void)hipFree(ctx->arena_dev);
+  if (ctx->arena_host) (void)hipHostFree(ctx->arena_host);
+  delete ctx;
+}
+
+// ---------------------------------------------------------------------------
+// a1: score
+// ---------------------------------------------------------------------------
+extern "C" hack_status hack_score(hack_ctx* ctx, int32_t B, int32_t N_k, const void* q, const int32_t* q_idx,
+                                  int32_t n_obs, float scale, const hack_cache* in, const void* k_new,
+                                  const uint8_t* active, float* importance, int64_t imp_stride,
+                                  hack_stream stream) {
+  hack_status st = check_common(ctx, B, N_k, true);
+  if (st != HACK_OK) return st;
+  const int U = B * ctx->cfg.heads;
+  if (!q || !importance) return fail(ctx, HACK_EINVAL, "q and importance must not be NULL");
+  if (!aligned16(q) || (k_new && !aligned16(k_new))) return fail(ctx, HACK_EINVAL, "q/k_new must be 16-byte aligned");
+  if (n_obs < 1 || n_obs > ctx->cfg.n_obs || n_obs > N_k)
+    return fail(ctx, HACK_EINVAL, "n_obs = %d outside [1, min(%d, N_k = %d)]", n_obs, ctx->cfg.n_obs, N_k);
+  if (!scale_ok(scale)) return fail(ctx, HACK_EINVAL, "scale must be finite and > 0");
+  if (q_idx)
+    for (int i = 0; i < n_obs; ++i)
+      if (q_idx[i] < 0 || q_idx[i] >= N_k) return fail(ctx, HACK_EINVAL, "q_idx[%d] = %d outside [0, %d)", i, q_idx[i], N_k);
+  if ((st = check_cache(ctx, in, U, "in", false)) != HACK_OK) return st;
+  const int n_new = k_new ? N_k : 0;
+  std::vector<UnitDesc> descs;
+  std::vector<int32_t> list;
+  int max_t = 0;
+  for (int u = 0; u < U; ++u) {
+    if (active && !active[u]) continue;
+    const int64_t T = (int64_t)in->len[u] + n_new;
+    if (T < 1) return fail(ctx, HACK_EINVAL, "unit %d has no keys to score", u);
+    if (T > ctx->cfg.max_cache_len) return fail(ctx, HACK_ECAPACITY, "unit %d: T_in = %lld exceeds max_cache_len %d", u, (long long)T, ctx->cfg.max_cache_len);
+    if (T > imp_stride) return fail(ctx, HACK_ECAPACITY, "imp_stride %lld < T_in %lld of unit %d", (long long)imp_stride, (long long)T, u);
+    UnitDesc d{};
+    d.in_off = in->off[u]; d.out_off = in->off[u]; d.len_in = in->len[u]; d.n_new = n_new; d.n_out = (int)T; d.unit = u;
+    list.push_back((int32_t)descs.size());
+    descs.push_back(d);
+    max_t = std::max(max_t, (int)T);
+  }
+  if (descs.empty()) return HACK_OK;
+  int32_t rows[kMaxObs];
+  fill_q_rows(q_idx, n_obs, N_k, rows);
+  Table t;
+  const size_t o_desc = t.add(descs.data(), descs.size());
+  const size_t o_list = t.add(list.data(), list.size());
+  const size_t o_rows = t.add(rows, kMaxObs);
+  const uint8_t* dev;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
+  launch_score(s, ctx->cfg.dtype, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), (const int32_t*)(dev + o_list),
+               (int)list.size(), max_t, q, (const int32_t*)(dev + o_rows), n_obs, N_k, scale, in->k, k_new,
+               ctx->stats, importance, imp_stride);
+  HIP_TRY(ctx, hipGetLastError());
+  return HACK_OK;
+}
+
+// ---------------------------------------------------------------------------
+// a2: select
+// ---------------------------------------------------------------------------
+extern "C" hack_status hack_select(hack_ctx* ctx, int32_t B, const float* importance, int64_t imp_stride,
+                                   const int32_t* t_in, const uint8_t* head_type, const int32_t* budget,
+                                   int32_t n_init, int32_t n_recent, int32_t* kept_idx, int64_t idx_stride,
+                                   int32_t* len_out, hack_stream stream) {
+  hack_status st = check_common(ctx, B, 0, false);
+  if (st != HACK_OK) return st;
+  const int U = B * ctx->cfg.heads, H = ctx->cfg.heads;
+  if (!importance || !t_in || !head_type || !budget || !kept_idx) return fail(ctx, HACK_EINVAL, "NULL argument");
+  if (n_init < 0 || n_recent < 0) return fail(ctx, HACK_EINVAL, "n_init and n_recent must be >= 0");
+  for (int h = 0; h < H; ++h)
+    if (head_type[h] > 1) return fail(ctx, HACK_EINVAL, "head_type[%d] = %d is not a head class", h, head_type[h]);
+  std::vector<UnitDesc> descs(U);
+  std::vector<int32_t> list(U);
+  int max_t = 0;
+  for (int u = 0; u < U; ++u) {
+    const int T = t_in[u];
+    if (T < 1) return fail(ctx, HACK_EINVAL, "t_in[%d] = %d", u, T);
+    if (T > ctx->cfg.max_cache_len) return fail(ctx, HACK_ECAPACITY, "t_in[%d] = %d exceeds max_cache_len %d", u, T, ctx->cfg.max_cache_len);
+    if (budget[u] < 1) return fail(ctx, HACK_EINVAL, "budget[%d] = %d", u, budget[u]);
+    if (head_type[u % H] == HACK_STRUCTURAL && n_recent > T) return fail(ctx, HACK_EINVAL, "n_recent %d > t_in[%d] = %d", n_recent, u, T);
+    const int b = std::min(budget[u], T);
+    if (T > imp_stride || b > idx_stride) return fail(ctx, HACK_ECAPACITY, "strides too small for unit %d", u);
+    UnitDesc d{};
+    d.len_in = T; d.n_new = 0; d.n_out = b; d.unit = u;
+    plan_select(head_type[u % H], T, b, n_init, n_recent, &d);
+    descs[u] = d;
+    list[u] = u;
+    max_t = std::max(max_t, T);
+    if (len_out) len_out[u] = b;
+  }
+  Table t;
+  const size_t o_desc = t.add(descs.data(), descs.size());
+  const size_t o_list = t.add(list.data(), list.size());
+  const uint8_t* dev;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
+  launch_select(s, (const UnitDesc*)(dev + o_desc), (const int32_t*)(dev + o_list), U, max_t, importance, imp_stride,
+                kept_idx, idx_stride);
+  HIP_TRY(ctx, hipGetLastError());
+  return HACK_OK;
+}
+
+// ---------------------------------------------------------------------------
+// a3: compact
+// ---------------------------------------------------------------------------
+extern "C" hack_status hack_compact(hack_ctx* ctx, int32_t B, int32_t N_k, const hack_cache* in, const void* k_new,
+                                    const void* v_new, int32_t pos_new, const int32_t* kept_idx, int64_t idx_stride,
+                                    const hack_cache* out, hack_stream stream) {
+  const bool has_new = (k_new != nullptr);
+  hack_status st = check_common(ctx, B, N_k, has_new);
+  if (st != HACK_OK) return st;
+  const int U = B * ctx->cfg.heads;
+  if (!kept_idx) return fail(ctx, HACK_EINVAL, "kept_idx is NULL");
+  if (has_new != (v_new != nullptr)) return fail(ctx, HACK_EINVAL, "k_new and v_new must both be given or both be NULL");
+  if (has_new && (!aligned16(k_new) || !aligned16(v_new))) return fail(ctx, HACK_EINVAL, "k_new/v_new must be 16-byte aligned");
+  if ((st = check_cache(ctx, in, U, "in", true)) != HACK_OK) return st;
+  if ((st = check_cache(ctx, out, U, "out", true)) != HACK_OK) return st;
+  const int n_new = has_new ? N_k : 0;
+  std::vector<UnitDesc> descs;
+  int max_rows = 0;
+  std::vector<std::pair<int64_t, int64_t>> in_iv;
+  for (int u = 0; u < U; ++u) {
+    const int n = out->len[u];
+    if (n == 0) continue;
+    if (n > idx_stride) return fail(ctx, HACK_ECAPACITY, "idx_stride %lld < out->len[%d] = %d", (long long)idx_stride, u, n);
+    if ((int64_t)n > (int64_t)in->len[u] + n_new) return fail(ctx, HACK_EINVAL, "unit %d keeps %d rows of %lld", u, n, (long long)in->len[u] + n_new);
+    UnitDesc d{};
+    d.in_off = in->off[u]; d.out_off = out->off[u]; d.len_in = in->len[u]; d.n_new = n_new; d.n_out = n;
+    d.mode = MOVE_GATHER; d.unit = u;
+    descs.push_back(d);
+    max_rows = std::max(max_rows, n);
+    if (in->len[u] > 0) in_iv.emplace_back(in->off[u], in->off[u] + in->len[u]);
+  }
+  if (descs.empty()) return HACK_OK;
+  if (out->k == in->k || out->v == in->v || out->k == in->v || out->v == in->k) {
+    std::sort(in_iv.begin(), in_iv.end());
+    for (const UnitDesc& d : descs) {
+      const int64_t a = d.out_off, b = d.out_off + d.n_out;
+      auto it = std::lower_bound(in_iv.begin(), in_iv.end(), std::make_pair(b, (int64_t)INT64_MIN));
+      // intervals starting before b: the one with the largest end among them may overlap
+      for (auto p = in_iv.begin(); p != it; ++p)
+        if (p->second > a) return fail(ctx, HACK_EINVAL, "output rows of unit %d overlap input rows that are read", d.unit);
+    }
+  }
+  Table t;
+  const size_t o_desc = t.add(descs.data(), descs.size());
+  const uint8_t* dev;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
+  CachePtrs pin{in->k, in->v, in->pos}, pout{out->k, out->v, out->pos};
+  launch_move(s, ctx->elem_bytes, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), (int)descs.size(), max_rows, pin,
+              pout, k_new, v_new, N_k, pos_new, kept_idx, idx_stride);
+  HIP_TRY(ctx, hipGetLastError());
+  return HACK_OK;
+}
+
+// ---------------------------------------------------------------------------
+// a4: attention
+// ---------------------------------------------------------------------------
+extern "C" hack_status hack_attn(hack_ctx* ctx, int32_t B, int32_t N_k, const void* q, const hack_cache* kv,
+                                 float scale, void* out, hack_stream stream) {
+  hack_status st = check_common(ctx, B, N_k, true);
+  if (st != HACK_OK) return st;
+  const int U = B * ctx->cfg.heads;
+  if (!q || !out) return fail(ctx, HACK_EINVAL, "q and out must not be NULL");
+  if (!aligned16(q) || !aligned16(out)) return fail(ctx, HACK_EINVAL, "q/out must be 16-byte aligned");
+  if (!scale_ok(scale)) return fail(ctx, HACK_EINVAL, "scale must be finite and > 0");
+  if ((st = check_cache(ctx, kv, U, "kv", true)) != HACK_OK) return st;
+  std::vector<UnitDesc> descs(U);
+  for (int u = 0; u < U; ++u) {
+    if (kv->len[u] < 1) return fail(ctx, HACK_EINVAL, "unit %d has an empty cache", u);
+    UnitDesc d{};
+    d.in_off = kv->off[u]; d.out_off = kv->off[u]; d.len_in = kv->len[u]; d.n_out = kv->len[u]; d.unit = u;
+    descs[u] = d;
+  }
+  const int tile = attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim);
+  std::vector<AttnItem> items;
+  build_attn_items(descs, N_k, tile, &items);
+  Table t;
+  const size_t o_desc = t.add(descs.data(), descs.size());
+  const size_t o_items = t.add(items.data(), items.size());
+  const uint8_t* dev;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
+  launch_attn(s, ctx->cfg.dtype, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), (const AttnItem*)(dev + o_items),
+              (int)items.size(), tile, q, kv->k, kv->v, N_k, scale, out);
+  HIP_TRY(ctx, hipGetLastError());
+  return HACK_OK;
+}
+
+// ---------------------------------------------------------------------------
+// a5: managed cache + fused step
+// ---------------------------------------------------------------------------
+extern "C" hack_status hack_kvcache_rows_required(int32_t n_units, const int32_t* cap, int64_t* rows) {
+  if (n_units < 1 || !cap || !rows) return HACK_EINVAL;
+  int64_t r = 0;
+  for (int u = 0; u < n_units; ++u) {
+    if (cap[u] < 1) return HACK_EINVAL;
+    r += 2 * round_up(cap[u], 8);
+  }
+  *rows = r;
+  return HACK_OK;
+}
+
+extern "C" hack_status hack_kvcache_create(hack_ctx* ctx, int32_t n_units, const int32_t* cap, void* k_mem,
+                                           void* v_mem, int32_t* pos_mem, int64_t mem_rows, hack_kvcache** out) {
+  if (!ctx) return HACK_EINVAL;
+  if (!out || !cap || !k_mem || !v_mem) return fail(ctx, HACK_EINVAL, "NULL argument");
+  *out = nullptr;
+  if (n_units < 1 || n_units > ctx->cfg.max_units || n_units % ctx->cfg.heads)
+    return fail(ctx, HACK_EINVAL, "n_units = %d must be a multiple of H within max_units", n_units);
+  if (!aligned16(k_mem) || !aligned16(v_mem)) return fail(ctx, HACK_EINVAL, "k_mem/v_mem must be 16-byte aligned");
+  int64_t need;
+  if (hack_kvcache_rows_required(n_units, cap, &need) != HACK_OK) return fail(ctx, HACK_EINVAL, "cap entries must be >= 1");
+  if (need > mem_rows) return fail(ctx, HACK_ECAPACITY, "cache needs %lld rows, %lld given", (long long)need, (long long)mem_rows);
+  hack_kvcache* c = new (std::nothrow) hack_kvcache();
+  if (!c) return fail(ctx, HACK_EHIP, "out of host memory");
+  c->ctx = ctx; c->n_units = n_units; c->k = k_mem; c->v = v_mem; c->pos = pos_mem; c->rows = mem_rows; c->tokens_seen = 0;
+  c->cap.assign(cap, cap + n_units);
+  c->slab[0].resize(n_units); c->slab[1].resize(n_units);
+  c->cur.assign(n_units, 0); c->len.assign(n_units, 0); c->off.resize(n_units);
+  int64_t r = 0;
+  for (int u = 0; u < n_units; ++u) {
+    c->slab[0][u] = r; r += round_up(cap[u], 8);
+    c->slab[1][u] = r; r += round_up(cap[u], 8);
+    c->off[u] = c->slab[0][u];
+  }
+  *out = c;
+  return HACK_OK;
+}
+
+extern "C" void hack_kvcache_destroy(hack_kvcache* c) { delete c; }
+
+extern "C" hack_status hack_kvcache_reset(hack_kvcache* c) {
+  if (!c) return HACK_EINVAL;
+  for (int u = 0; u < c->n_units; ++u) {
+    c->len[u] = 0; c->cur[u] = 0; c->off[u] = c->slab[0][u];
+  }
+  c->tokens_seen = 0;
+  return HACK_OK;
+}
+
+extern "C" hack_status hack_kvcache_view(const hack_kvcache* c, hack_cache* view) {
+  if (!c || !view) return HACK_EINVAL;
+  view->k = c->k; view->v = c->v; view->pos = c->pos; view->rows = c->rows;
+  view->off = c->off.data(); view->len = c->len.data();
+  return HACK_OK;
+}
+
+extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, int32_t N_k, const void* q,
+                                 const void* k_new, const void* v_new, const uint8_t* head_type,
+                                 const int32_t* budget, int32_t n_init, float scale, void* out,
+                                 int32_t* kept_idx_opt, int64_t idx_stride, hack_stream stream) {
+  hack_status st = check_common(ctx, B, N_k, true);
+  if (st != HACK_OK) return st;
+  const int U = B * ctx->cfg.heads, H = ctx->cfg.heads;
+  if (!cache || cache->ctx != ctx || cache->n_units != U) return fail(ctx, HACK_EINVAL, "cache does not belong to this context / batch");
+  if (!q || !k_new || !v_new || !head_type || !budget || !out) return fail(ctx, HACK_EINVAL, "NULL argument");
+  if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out)) return fail(ctx, HACK_EINVAL, "q/k_new/v_new/out must be 16-byte aligned");
+  if (!scale_ok(scale)) return fail(ctx, HACK_EINVAL, "scale must be finite and > 0");
+  if (n_init < 0) return fail(ctx, HACK_EINVAL, "n_init must be >= 0");
+  for (int h = 0; h < H; ++h)
+    if (head_type[h] > 1) return fail(ctx, HACK_EINVAL, "head_type[%d] = %d is not a head class", h, head_type[h]);
+  if (cache->tokens_seen + N_k > INT32_MAX) return fail(ctx, HACK_ECAPACITY, "token ids overflow int32");
+
+  int32_t* kept = kept_idx_opt ? kept_idx_opt : ctx->kept;
+  const int64_t kstride = kept_idx_opt ? idx_stride : ctx->ws_stride;
+  std::vector<UnitDesc> descs(U);
+  std::vector<int32_t> comp;
+  int max_t = 0, max_rows = 0;
+  for (int u = 0; u < U; ++u) {
+    const int L = cache->len[u];
+    const int64_t T = (int64_t)L + N_k;
+    if (budget[u] < 1) return fail(ctx, HACK_EINVAL, "budget[%d] = %d", u, budget[u]);
+    UnitDesc d{};
+    d.unit = u; d.in_off = cache->off[u]; d.len_in = L; d.n_new = N_k;
+    if (budget[u] < T) {
+      if (T > ctx->cfg.max_cache_len) return fail(ctx, HACK_ECAPACITY, "unit %d: T_in = %lld exceeds max_cache_len %d", u, (long long)T, ctx->cfg.max_cache_len);
+      if (budget[u] > cache->cap[u]) return fail(ctx, HACK_ECAPACITY, "unit %d: budget %d exceeds its slab of %d rows", u, budget[u], cache->cap[u]);
+      if (budget[u] > kstride) return fail(ctx, HACK_ECAPACITY, "idx_stride %lld < budget[%d] = %d", (long long)kstride, u, budget[u]);
+      d.mode = MOVE_GATHER; d.n_out = budget[u]; d.out_off = cache->slab[cache->cur[u] ^ 1][u];
+      plan_select(head_type[u % H], (int)T, budget[u], n_init, N_k, &d);
+      comp.push_back(u);
+      max_t = std::max(max_t, (int)T);
+      max_rows = std::max(max_rows, d.n_out);
+    } else {
+      if (T > cache->cap[u]) return fail(ctx, HACK_ECAPACITY, "unit %d: %lld rows do not fit its slab of %d", u, (long long)T, cache->cap[u]);
+      d.mode = MOVE_APPEND; d.n_out = (int)T; d.out_off = cache->off[u];
+      max_rows = std::max(max_rows, N_k);
+    }
+    descs[u] = d;
+  }
+  const int n_obs = std::min(ctx->cfg.n_obs, N_k);
+  int32_t rows[kMaxObs];
+  fill_q_rows(nullptr, n_obs, N_k, rows);
+  const int tile = attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim);
+  std::vector<AttnItem> items;
+  build_attn_items(descs, N_k, tile, &items);
+
+  Table t;
+  const size_t o_desc = t.add(descs.data(), descs.size());
+  const size_t o_comp = t.add(comp.data(), comp.size());
+  const size_t o_rows = t.add(rows, kMaxObs);
+  const size_t o_items = t.add(items.data(), items.size());
+  const uint8_t* dev;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
+  const UnitDesc* ddev = (const UnitDesc*)(dev + o_desc);
+  CachePtrs cp{cache->k, cache->v, cache->pos};
+
+  if (!comp.empty()) {
+    launch_score(s, ctx->cfg.dtype, ctx->cfg.head_dim, ddev, (const int32_t*)(dev + o_comp), (int)comp.size(), max_t, q,
+                 (const int32_t*)(dev + o_rows), n_obs, N_k, scale, cache->k, k_new, ctx->stats, ctx->importance,
+                 ctx->ws_stride);
+    launch_select(s, ddev, (const int32_t*)(dev + o_comp), (int)comp.size(), max_t, ctx->importance, ctx->ws_stride, kept,
+                  kstride);
+  }
+  launch_move(s, ctx->elem_bytes, ctx->cfg.head_dim, ddev, U, max_rows, cp, cp, k_new, v_new, N_k,
+              (int32_t)cache->tokens_seen, kept, kstride);
+  launch_attn(s, ctx->cfg.dtype, ctx->cfg.head_dim, ddev, (const AttnItem*)(dev + o_items), (int)items.size(), tile, q,
+              cache->k, cache->v, N_k, scale, out);
+  HIP_TRY(ctx, hipGetLastError());
+
+  for (int u = 0; u < U; ++u) {
+    if (descs[u].mode == MOVE_GATHER) {
+      cache->cur[u] ^= 1;
+      cache->off[u] = cache->slab[cache->cur[u]][u];
+    }
+    cache->len[u] = descs[u].n_out;
+  }
+  cache->tokens_seen += N_k;
+  return HACK_OK;
+}

@@ -1,0 +1,76 @@
+// Internal declarations shared by the host side (hack_api.cpp) and the HIP
+// kernels of the gfx950 library.  Nothing here is part of the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace hack {
+
+// Per-unit launch table entry, built on the host from the caller's host arrays
+// and uploaded once per distinct table.  One unit = one (batch, head) pair.
+struct alignas(16) UnitDesc {
+  int64_t in_off;   // first row of the unit's input rows in the cache arrays
+  int64_t out_off;  // first row of its output rows (gather target / attention source)
+  int32_t len_in;   // cache rows before this step (L)
+  int32_t n_new;    // rows of the current scale that virtually follow them (0 or N_k)
+  int32_t n_out;    // rows to produce (gather) or rows attended over
+  int32_t keep_a;   // select: rows [0, keep_a) are always kept
+  int32_t sel_lo;   // select: ranked segment [sel_lo, sel_hi)
+  int32_t sel_hi;
+  int32_t sel_m;    // select: how many rows of the ranked segment are kept
+  int32_t keep_b;   // select: rows [keep_b, T_in) are always kept
+  int32_t mode;     // move kernel: MOVE_* below
+  int32_t unit;     // unit id u = b*H + h (rows of q/k_new/out start at u*N_k)
+  int32_t pad0;
+  int32_t pad1;
+};
+static_assert(sizeof(UnitDesc) == 64, "UnitDesc must stay 64 bytes");
+
+enum : int32_t { MOVE_NONE = 0, MOVE_APPEND = 1, MOVE_GATHER = 2 };
+
+// One attention work item: a tile of queries of one unit.
+struct AttnItem {
+  int32_t desc;    // index into the UnitDesc table
+  int32_t q_tile;  // first query row = q_tile * (rows per tile)
+};
+
+struct CachePtrs {
+  void* k;
+  void* v;
+  int32_t* pos;
+};
+
+constexpr int kScoreChunk = 256;   // keys per score work-group
+constexpr int kMaxObs = 32;        // observation queries (one MFMA column block)
+
+// ---- kernel launchers (each validates nothing: the API layer has done so) ----
+
+// Append / gather K, V (and pos) rows.  `descs` has n_desc entries; every entry
+// with mode != MOVE_NONE is processed.  max_rows = max over entries of the rows
+// it moves.
+void launch_move(hipStream_t s, int elem_bytes, int head_dim, const UnitDesc* descs, int n_desc,
+                 int max_rows, CachePtrs in, CachePtrs out, const void* k_new, const void* v_new,
+                 int N_k, int pos_new, const int32_t* kept_idx, int64_t idx_stride);
+
+// Subset-attention importance.  list[n_list] indexes descs; stats is a
+// workspace of n_list * max_chunks * 64 doubles; q_rows DEVICE int32[n_obs].
+void launch_score(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, const int32_t* list,
+                  int n_list, int max_t_in, const void* q, const int32_t* q_rows, int n_obs, int N_k,
+                  float scale, const void* k_cache, const void* k_new, double* stats,
+                  float* importance, int64_t imp_stride);
+
+// Budgeted selection; one work-group per listed unit.
+void launch_select(hipStream_t s, const UnitDesc* descs, const int32_t* list, int n_list,
+                   int max_t_in, const float* importance, int64_t imp_stride, int32_t* kept_idx,
+                   int64_t idx_stride);
+size_t select_lds_bytes(int max_t_in);
+
+// Attention of N_k queries per unit over rows [out_off, out_off + n_out).
+void launch_attn(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, const AttnItem* items,
+                 int n_items, int q_tile_rows, const void* q, const void* k_cache,
+                 const void* v_cache, int N_k, float scale, void* out);
+// Query rows per attention work item for this dtype/head_dim.
+int attn_q_tile_rows(int dtype, int head_dim);
+
+}  // namespace hack

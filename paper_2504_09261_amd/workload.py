@@ -85,7 +85,8 @@ class Config:
 
     @property
     def scale(self) -> float:
-        return 1.0 / math.sqrt(self.head_dim)
+        # exactly the float32 the library receives, so both sides scale alike
+        return float(np.float32(1.0 / math.sqrt(self.head_dim)))
 
     @property
     def elem_bytes(self) -> int:

@@ -1,0 +1,186 @@
+"""Whole-schedule GPU-vs-oracle parity (fused hack_step, free-running) and a
+teacher-forced pass through the individual calls, on the seeded synthetic
+VAR / Infinity-shaped workloads."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hack_oracle as ho
+from paper_2504_09261_amd import workload as wl
+from paper_2504_09261_amd.binding import Cache
+
+pytestmark = pytest.mark.gpu
+
+
+def _u():
+    from tests import gpu_util
+    return gpu_util
+
+
+def _tol(cfg):
+    return 1e-4 if cfg.dtype == "f32" else 2e-2
+
+
+def run_free(cfg, layer, units, steps=None):
+    """hack_step over the schedule on all units; oracle on `units`.  Returns statistics."""
+    u = _u()
+    hk = u.make_hack(cfg)
+    types = wl.head_types(cfg, layer)
+    cap = np.minimum(np.tile(wl.head_budgets(cfg, layer), cfg.batch), cfg.T_K)
+    mc = hk.managed_cache(cap)
+    n_steps = cfg.n_steps if steps is None else steps
+    data = wl.gen_layer(cfg, layer, range(1, n_steps + 1))
+    budgets = [wl.step_budgets(cfg, layer, k) for k in range(1, n_steps + 1)]
+    trace = ho.run_schedule([(data[k].q, data[k].k, data[k].v) for k in range(1, n_steps + 1)], types, budgets,
+                            cfg.n_init, cfg.scale, cfg.n_obs, units=units)
+    plan = wl.planned_lengths(cfg, layer)
+    stats = dict(exact=0, excused=0, mismatch=0, max_err=0.0, compress_events=0)
+    diverged = set()
+    stride = (cfg.T_K + 63) // 64 * 64
+    for k in range(1, n_steps + 1):
+        st = data[k]
+        q, kn, vn = u.to_dev(st.q, cfg.dtype), u.to_dev(st.k, cfg.dtype), u.to_dev(st.v, cfg.dtype)
+        out = torch.empty_like(q)
+        kept = torch.full((cfg.n_units, stride), -1, dtype=torch.int32, device=u.DEV)
+        hk.step(mc, q, kn, vn, types, budgets[k - 1], cfg.n_init, cfg.scale, out, kept_idx=kept)
+        torch.cuda.synchronize()
+        off, ln = mc.view()
+        assert np.array_equal(ln, plan[k - 1][2])                 # lengths are host-planned
+        got, kept_h, pos_h = u.from_dev(out), kept.cpu().numpy(), mc.pos.cpu().numpy()
+        for uu in units:
+            if uu in diverged:
+                continue
+            b, h = divmod(uu, cfg.heads)
+            r = trace[k - 1][uu]
+            T_in = int(plan[k - 1][1][uu])
+            if r["compressed"]:
+                stats["compress_events"] += 1
+                I_gpu = kept_h[uu, :len(r["I"])]
+                lo, hi, m = u.ranked_segment(int(types[h]), T_in, len(r["I"]), cfg.n_init, st.N_k)
+                verdict = u.kept_set_verdict(I_gpu, r["I"], r["imp"], lo, hi, m)
+                stats[verdict] += 1
+                assert verdict != "mismatch", (k, uu)
+                if verdict == "excused":
+                    diverged.add(uu)          # its later steps see a different (equally valid) cache
+                    continue
+            assert np.array_equal(pos_h[off[uu]:off[uu] + ln[uu]], r["pos"]), (k, uu)
+            err = np.abs(got[b, h] - r["O"]).max()
+            stats["max_err"] = max(stats["max_err"], float(err))
+            assert err < _tol(cfg), (k, uu, err)
+    # cache contents of non-diverged units are bit-exact copies of the inputs
+    Kc, Vc = u.from_dev(mc.k), u.from_dev(mc.v)
+    for uu in units:
+        if uu in diverged:
+            continue
+        r = trace[n_steps - 1][uu]
+        assert np.array_equal(Kc[off[uu]:off[uu] + ln[uu]], r["K"]) and np.array_equal(Vc[off[uu]:off[uu] + ln[uu]], r["V"])
+    mc.close()
+    hk.close()
+    return stats
+
+
+def test_cfg0_fp32_full_schedule_all_units():
+    cfg = wl.get_config(0)
+    stats = run_free(cfg, 0, list(range(cfg.n_units)))
+    assert stats["compress_events"] == 8 * 4 + 8 * 2
+    assert stats["mismatch"] == 0 and stats["excused"] == 0     # fp64 logits: exact kept sets
+
+
+def test_cfg1_shape_reduced_batch_full_schedule():
+    cfg = wl.get_config(1, batch=3)
+    stats = run_free(cfg, 1, list(range(0, cfg.n_units, 7)))
+    assert stats["mismatch"] == 0 and stats["compress_events"] > 0
+
+
+def test_cfg2_full_size_sampled_units():
+    cfg = wl.get_config(2)
+    types = wl.head_types(cfg, 0)
+    ctx = [int(h) for h in np.where(types == 0)[0][:1]]
+    st = [int(h) for h in np.where(types == 1)[0][:2]]
+    units = ctx + st + [cfg.heads + st[0]]                          # second batch element too
+    stats = run_free(cfg, 0, units)
+    assert stats["mismatch"] == 0 and stats["compress_events"] >= 4 + 3 * 3
+
+
+def test_cfg4_ragged_budgets_small_batch():
+    cfg = wl.get_config(4, keep=0.5, ctx_frac=0.25, batch=1)
+    stats = run_free(cfg, 2, [0, 3, 5, 11], steps=11)
+    assert stats["mismatch"] == 0 and stats["compress_events"] > 0
+
+
+def test_teacher_forced_steps_through_individual_calls():
+    """Each step starts from the oracle's cache, so one divergence cannot cascade;
+    select is fed the oracle's float32 importance and must be bit-exact."""
+    u = _u()
+    cfg = wl.get_config(1, batch=1)
+    layer = 0
+    hk = u.make_hack(cfg)
+    types = wl.head_types(cfg, layer)
+    data = wl.gen_layer(cfg, layer)
+    budgets = [wl.step_budgets(cfg, layer, k) for k in range(1, cfg.n_steps + 1)]
+    units = list(range(cfg.n_units))
+    trace = ho.run_schedule([(data[k].q, data[k].k, data[k].v) for k in range(1, cfg.n_steps + 1)], types, budgets,
+                            cfg.n_init, cfg.scale, cfg.n_obs)
+    U, d, H = cfg.n_units, cfg.head_dim, cfg.heads
+    stride = 704
+    for k in range(2, cfg.n_steps + 1):
+        st = data[k]
+        prev = trace[k - 2]
+        rows = [(prev[uu]["K"].astype(np.float32), prev[uu]["V"].astype(np.float32)) for uu in units]
+        cin, _ = u.build_cache(rows, d, cfg.dtype)
+        q, kn, vn = u.to_dev(st.q, cfg.dtype), u.to_dev(st.k, cfg.dtype), u.to_dev(st.v, cfg.dtype)
+        t_in = np.array([r[0].shape[0] + st.N_k for r in rows], np.int32)
+        comp = np.array([trace[k - 1][uu]["compressed"] for uu in units])
+        imp = torch.zeros((U, stride), device=u.DEV)
+        hk.score(q, cin, cfg.scale, imp, k_new=kn, active=comp.astype(np.uint8))
+        torch.cuda.synchronize()
+        imp_h = imp.cpu().numpy()
+        imp_ref = np.zeros((U, stride), np.float32)
+        for uu in units:
+            if comp[uu]:
+                ref = trace[k - 1][uu]["imp"]
+                worst = float(np.max(np.abs(imp_h[uu, :t_in[uu]] - ref) / ref))
+                assert worst < 1e-6, (k, uu, worst)
+                imp_ref[uu, :t_in[uu]] = ref.astype(np.float32)
+        kept = torch.full((U, stride), -1, dtype=torch.int32, device=u.DEV)
+        len_out = hk.select(1, torch.from_numpy(imp_ref).to(u.DEV), t_in, types, budgets[k - 1], cfg.n_init, st.N_k, kept)
+        torch.cuda.synchronize()
+        kept_h = kept.cpu().numpy()
+        for uu in units:
+            want = trace[k - 1][uu]["I"] if comp[uu] else np.arange(t_in[uu])
+            assert np.array_equal(kept_h[uu, :len_out[uu]], want), (k, uu)
+        off_out, total = u.aligned_offsets(len_out)
+        cout = Cache(torch.zeros((total, d), dtype=hk.torch_dtype, device=u.DEV),
+                     torch.zeros((total, d), dtype=hk.torch_dtype, device=u.DEV), off_out, len_out)
+        hk.compact(1, st.N_k, cin, kept, cout, kn, vn)
+        out = torch.empty_like(q)
+        hk.attn(q, cout, cfg.scale, out)
+        torch.cuda.synchronize()
+        Kc, got = u.from_dev(cout.k), u.from_dev(out)
+        for uu in units:
+            r = trace[k - 1][uu]
+            assert np.array_equal(Kc[off_out[uu]:off_out[uu] + len_out[uu]], r["K"])
+            assert np.abs(got[0, uu] - r["O"]).max() < 2e-2
+    hk.close()
+
+
+def test_step_capacity_and_argument_errors():
+    u = _u()
+    from paper_2504_09261_amd.binding import HackError
+    hk = u.make_hack(heads=2, head_dim=64, dtype="bf16", max_units=2, max_cache_len=64, max_queries=16)
+    mc = hk.managed_cache([20, 20])
+    q = torch.zeros((1, 2, 16, 64), dtype=torch.bfloat16, device=u.DEV)
+    out = torch.empty_like(q)
+    hk.step(mc, q, q, q, [0, 1], [1 << 30, 1 << 30], 5, 0.125, out)
+    with pytest.raises(HackError):        # 32 rows do not fit a 20-row slab without compression
+        hk.step(mc, q, q, q, [0, 1], [1 << 30, 1 << 30], 5, 0.125, out)
+    off, ln = mc.view()
+    assert list(ln) == [16, 16]            # failed call left the state untouched
+    with pytest.raises(HackError):        # budget above the slab
+        hk.step(mc, q, q, q, [0, 1], [24, 24], 5, 0.125, out)
+    hk.step(mc, q, q, q, [0, 1], [20, 18], 5, 0.125, out)
+    torch.cuda.synchronize()
+    assert list(mc.view()[1]) == [20, 18]
+    mc.reset()
+    assert list(mc.view()[1]) == [0, 0]
+    hk.close()
