@@ -1,0 +1,265 @@
+#!/usr/bin/env python3
+"""Benchmark of the HACK hot path on one MI355X.
+
+One "step" = one layer's whole scale schedule (score -> select -> compact ->
+attend at every scale) on a batch of seeded synthetic inputs that are already
+resident in HBM.  Prints ONE JSON line: full-schedule us/layer, plus the
+roofline of the dominant kernel (attention, bf16 MFMA), per-stage rates and the
+fp64 oracle timed on the host cores (a baseline, not the target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
+HBM_PEAK_GBPS = 8000.0             # MI355X HBM3E
+FP32_VALU_PEAK_TFLOPS = 157.3
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--config", type=int, default=2, help="workload family 0..4 (default: Infinity-2B-shaped 1024^2)")
+    ap.add_argument("--layers", type=int, default=2, help="distinct layers of inputs kept resident and cycled")
+    ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-breakdown", action="store_true")
+    ap.add_argument("--batch", type=int, default=None)
+    return ap.parse_args()
+
+
+class LayerState:
+    """Inputs of one layer resident on the device + its managed cache."""
+
+    def __init__(self, hk, cfg, layer, wl, torch):
+        self.cfg, self.layer = cfg, layer
+        self.types = wl.head_types(cfg, layer)
+        self.budgets = [wl.step_budgets(cfg, layer, k) for k in range(1, cfg.n_steps + 1)]
+        cap = np.minimum(np.tile(wl.head_budgets(cfg, layer), cfg.batch), cfg.T_K)
+        self.mc = hk.managed_cache(cap, with_pos=True)
+        dev = torch.device("cuda", 0)
+        self.q, self.k, self.v, self.o = [], [], [], []
+        data = wl.gen_layer(cfg, layer)
+        for kk in range(1, cfg.n_steps + 1):
+            st = data[kk]
+            for dst, src_f, src_b in ((self.q, st.q, st.q_bits), (self.k, st.k, st.k_bits), (self.v, st.v, st.v_bits)):
+                if cfg.dtype == "bf16":
+                    t = torch.from_numpy(src_b.view(np.int16)).to(dev).view(torch.bfloat16)
+                else:
+                    t = torch.from_numpy(src_f).to(dev)
+                dst.append(t.contiguous())
+            self.o.append(torch.empty_like(self.q[-1]))
+        self.host = data
+
+    def run(self, hk):
+        c = self.cfg
+        self.mc.reset()
+        for i in range(c.n_steps):
+            hk.step(self.mc, self.q[i], self.k[i], self.v[i], self.types, self.budgets[i], c.n_init, c.scale, self.o[i])
+
+
+def time_events(torch, fn, reps):
+    """Average ms of fn() over reps launches, HIP events on the current stream."""
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in evs:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return float(np.mean([a.elapsed_time(b) for a, b in evs]))
+
+
+def breakdown(hk, ls, wl, torch, reps=5):
+    """Per-stage time of one layer: the same kernels hack_step launches, issued
+    through the individual entry points on the same cache states, each bracketed
+    by HIP events.  Returns dict stage -> list of ms per scale step."""
+    from paper_2504_09261_amd.binding import Cache
+    c = ls.cfg
+    dev = torch.device("cuda", 0)
+    stride = (c.T_K + 63) // 64 * 64
+    imp = torch.zeros((c.n_units, stride), device=dev)
+    kept = torch.zeros((c.n_units, stride), dtype=torch.int32, device=dev)
+    cap = np.minimum(np.tile(wl.head_budgets(c, ls.layer), c.batch), c.T_K)
+    off_s = np.concatenate([[0], np.cumsum((cap + 7) // 8 * 8)])[:-1].astype(np.int64)
+    rows_s = int(((cap + 7) // 8 * 8).sum())
+    ks = torch.empty((rows_s, c.head_dim), dtype=hk.torch_dtype, device=dev)
+    vs = torch.empty_like(ks)
+    t = dict(score=[], select=[], compact=[], attn=[])
+    ls.mc.reset()
+    plan = wl.planned_lengths(c, ls.layer)
+    for i in range(c.n_steps):
+        L, t_in, len_out = plan[i]
+        comp = (len_out < t_in)
+        if comp.any():
+            pre = ls.mc.as_cache()
+            act = comp.astype(np.uint8)
+            t["score"].append(time_events(torch, lambda: hk.score(ls.q[i], pre, c.scale, imp, k_new=ls.k[i], active=act), reps))
+            # select / compact are timed on the compressing units only, as in hack_step
+            bud = np.where(comp, ls.budgets[i], 1 << 30).astype(np.int32)
+            t["select"].append(time_events(torch, lambda: hk.select(c.batch, imp, t_in.astype(np.int32), ls.types, bud, c.n_init, c.N[i], kept), reps))
+            out_len = np.where(comp, len_out, 0).astype(np.int32)
+            scratch = Cache(ks, vs, off_s, out_len)
+            t["compact"].append(time_events(torch, lambda: hk.compact(c.batch, c.N[i], pre, kept, scratch, ls.k[i], ls.v[i]), reps))
+        else:
+            for s in ("score", "select", "compact"):
+                t[s].append(0.0)
+        hk.step(ls.mc, ls.q[i], ls.k[i], ls.v[i], ls.types, ls.budgets[i], c.n_init, c.scale, ls.o[i])
+        post = ls.mc.as_cache()
+        t["attn"].append(time_events(torch, lambda: hk.attn(ls.q[i], post, c.scale, ls.o[i]), reps))
+    return t
+
+
+def cpu_baseline(cfg, layer, wl, budget_s=20.0):
+    """The oracle as it stands, on the host cores, on a bounded sample of units."""
+    from oracle import hack_oracle as ho
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    types = wl.head_types(cfg, layer)
+    data = wl.gen_layer(cfg, layer)
+    steps = [(data[k].q, data[k].k, data[k].v) for k in range(1, cfg.n_steps + 1)]
+    budgets = [wl.step_budgets(cfg, layer, k) for k in range(1, cfg.n_steps + 1)]
+    ctx = [int(h) for h in np.where(types == 0)[0]]
+    st = [int(h) for h in np.where(types == 1)[0]]
+    sample, spent = [], 0.0
+    # alternate classes so the sample keeps the workload's contextual/structural mix in view
+    order = [u for pair in zip(st, ctx + st) for u in pair]
+    seen = set()
+    t_per = {}
+    for u in order:
+        if u in seen:
+            continue
+        seen.add(u)
+        t0 = time.perf_counter()
+        ho.run_schedule(steps, types, budgets, cfg.n_init, cfg.scale, cfg.n_obs, units=[u], keep_outputs=False)
+        dt = time.perf_counter() - t0
+        t_per.setdefault(int(types[u % cfg.heads]), []).append(dt)
+        sample.append(u)
+        spent += dt
+        if spent > budget_s or len(sample) >= 4:
+            break
+    n_c = int((np.tile(types, cfg.batch) == 0).sum())
+    n_s = cfg.n_units - n_c
+    mean_c = float(np.mean(t_per.get(0, t_per.get(1))))
+    mean_s = float(np.mean(t_per.get(1, t_per.get(0))))
+    layer_s = n_c * mean_c + n_s * mean_s
+    return dict(value=layer_s * 1e6, unit="us/layer", cores=int(cores), kind="oracle",
+                sample=f"{len(sample)} of {cfg.n_units} units of layer {layer} ({sample}), whole schedule each, "
+                       f"{spent:.1f} s measured, scaled by class counts ({n_c} contextual, {n_s} structural)")
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (units are independent; there is no multi-GPU path); "
+              "run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2504_09261_amd import workload as wl
+    from paper_2504_09261_amd.binding import Hack
+
+    cfg = wl.get_config(args.config, batch=args.batch)
+    torch.cuda.set_device(0)
+    hk = Hack(cfg.heads, cfg.head_dim, cfg.dtype, cfg.n_units, cfg.T_K, max(cfg.N), cfg.n_obs)
+    layers = [LayerState(hk, cfg, l, wl, torch) for l in range(args.layers)]
+
+    # eager warm-up: uploads every launch table once
+    for ls in layers:
+        ls.run(hk)
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.Stream()
+    graphs = None
+    if args.mode == "graph":
+        graphs = []
+        with torch.cuda.stream(stream):
+            for ls in layers:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=stream):
+                    ls.run(hk)
+                graphs.append(g)
+        torch.cuda.synchronize()
+
+    def one(i):
+        if graphs is not None:
+            graphs[i % len(layers)].replay()
+        else:
+            layers[i % len(layers)].run(hk)
+
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            one(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            one(i)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    work = wl.work_model(cfg, 0)
+    tot = {k: sum(r[k] for r in work) for k in work[0] if k not in ("k", "N_k")}
+    result = {
+        "metric": "full-schedule us/layer", "value": ms_per_step * 1e3, "unit": "us/layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "units": cfg.n_units, "heads": cfg.heads, "head_dim": cfg.head_dim,
+                   "batch": cfg.batch, "scales": len(cfg.sides), "tokens": cfg.T_K, "launch": args.mode,
+                   "layers_resident": args.layers},
+        "attn_gflop_per_layer": tot["attn_flop"] / 1e9,
+        "compress_mb_per_layer": (tot["score_bytes"] + tot["select_bytes"] + tot["compact_bytes"]) / 1e6,
+    }
+
+    if not args.no_breakdown:
+        bd = breakdown(hk, layers[0], wl, torch)
+        attn_ms = sum(bd["attn"])
+        n_attn = len(bd["attn"])
+        tf = tot["attn_flop"] / (attn_ms * 1e-3) / 1e12
+        big = [i for i, r in enumerate(work) if r["attn_flop"] > 0.05 * tot["attn_flop"]]
+        tf_big = sum(work[i]["attn_flop"] for i in big) / (sum(bd["attn"][i] for i in big) * 1e-3) / 1e12
+        result["roofline"] = {
+            "bound": "mfma", "kernel": "attn_mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+            "launches_per_layer": n_attn, "avg_launch_us": attn_ms * 1e3 / n_attn,
+            "flop_per_launch": tot["attn_flop"] / n_attn,
+            "large_steps": {"steps": [i + 1 for i in big], "achieved": tf_big,
+                            "frac": tf_big / MFMA_BF16_PEAK_TFLOPS},
+        } if cfg.dtype == "bf16" else {
+            "bound": "alu", "kernel": "attn_generic", "achieved": tf, "peak": FP32_VALU_PEAK_TFLOPS,
+            "unit": "TFLOP/s", "frac": tf / FP32_VALU_PEAK_TFLOPS, "traffic": None,
+        }
+        stages = {}
+        for s, key in (("score", "score_bytes"), ("select", "select_bytes"), ("compact", "compact_bytes")):
+            ms = sum(bd[s])
+            stages[s] = {"us_per_layer": ms * 1e3, "algorithmic_MB": tot[key] / 1e6,
+                         "GBps": (tot[key] / 1e9) / (ms * 1e-3) if ms > 0 else None,
+                         "frac_hbm": (tot[key] / 1e9) / (ms * 1e-3) / HBM_PEAK_GBPS if ms > 0 else None}
+        ssc_ms = sum(sum(bd[s]) for s in ("score", "select", "compact"))
+        ssc_b = tot["score_bytes"] + tot["select_bytes"] + tot["compact_bytes"]
+        stages["score+select+compact"] = {"us_per_layer": ssc_ms * 1e3, "GBps": ssc_b / 1e9 / (ssc_ms * 1e-3) if ssc_ms else None,
+                                          "frac_hbm": ssc_b / 1e9 / (ssc_ms * 1e-3) / HBM_PEAK_GBPS if ssc_ms else None}
+        stages["attn"] = {"us_per_layer": attn_ms * 1e3, "per_step_us": [round(x * 1e3, 1) for x in bd["attn"]]}
+        result["stages"] = stages
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(cfg, 0, wl)
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -448,7 +448,7 @@ extern "C" hack_status hack_attn(hack_ctx* ctx, int32_t B, int32_t N_k, const vo
     d.in_off = kv->off[u]; d.out_off = kv->off[u]; d.len_in = kv->len[u]; d.n_out = kv->len[u]; d.unit = u;
     descs[u] = d;
   }
-  const int tile = attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim);
+  const int tile = attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim, U, N_k);
   std::vector<AttnItem> items;
   build_attn_items(descs, N_k, tile, &items);
   Table t;
@@ -568,7 +568,7 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
   const int n_obs = std::min(ctx->cfg.n_obs, N_k);
   int32_t rows[kMaxObs];
   fill_q_rows(nullptr, n_obs, N_k, rows);
-  const int tile = attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim);
+  const int tile = attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim, U, N_k);
   std::vector<AttnItem> items;
   build_attn_items(descs, N_k, tile, &items);
 

@@ -70,7 +70,7 @@ size_t select_lds_bytes(int max_t_in);
 void launch_attn(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, const AttnItem* items,
                  int n_items, int q_tile_rows, const void* q, const void* k_cache,
                  const void* v_cache, int N_k, float scale, void* out);
-// Query rows per attention work item for this dtype/head_dim.
-int attn_q_tile_rows(int dtype, int head_dim);
+// Query rows per attention work item for this dtype/head_dim and launch size.
+int attn_q_tile_rows(int dtype, int head_dim, int n_units, int N_k);
 
 }  // namespace hack

@@ -13,8 +13,9 @@
 //     B operand (C rows 8(r/4)+4h+r%4 of registers 8s..8s+7 are exactly two runs
 //     of four consecutive keys), and V^T comes from row-major V in LDS through
 //     the transposing LDS read (ds_read_b64_tr_b16), four keys per read.
-//   * LDS rows are padded (K +16 B, V +32 B) so the b128 K reads and the
-//     transposing V reads are bank-conflict free.
+//   * K/V tiles are double-buffered and loaded HBM -> LDS directly (no register
+//     round trip), one barrier per tile; an XOR swizzle of 16-byte chunks keeps
+//     the b128 K reads and the transposing V reads bank-conflict free.
 // fp32 path: one query per lane, fp32 FMA, K/V rows broadcast from LDS; exact
 // enough for the 1e-4 bar and only used for the small fp32 configuration.
 #include "hack_internal.h"
@@ -96,8 +97,6 @@ __global__ __launch_bounds__(kGenQ) void attn_generic(
 // bf16 MFMA path
 // ---------------------------------------------------------------------------
 constexpr int kKT = 64;      // keys per LDS tile
-constexpr int kKPad = 8;     // bf16 elements of padding per K row (16 B)
-constexpr int kVPad = 16;    // bf16 elements of padding per V row (32 B)
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
   shortx4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -105,171 +104,179 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
   return __builtin_bit_cast(bf16x4, v);
 }
 
-template <int D, int NQB>
-__global__ __launch_bounds__(256) void attn_mfma(
+// K/V tiles go from HBM straight into LDS (global_load_lds, 16 B per lane, one
+// contiguous KiB per wave instruction), so LDS rows cannot be padded; bank
+// conflicts are avoided by a swizzle instead: the 16-byte chunk at position c of
+// LDS row r holds global chunk c ^ f(r), with f_K(r) = r & 7 (b128 operand reads
+// walk 8 consecutive rows) and f_V(r) = 2 (r & 3) (transposing reads walk 4
+// consecutive rows, 32 bytes each).
+__device__ __forceinline__ int swz_k(int r) { return r & 7; }
+__device__ __forceinline__ int swz_v(int r) { return 2 * (r & 3); }
+
+__device__ __forceinline__ void load_to_lds(const __bf16* src, __bf16* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+
+// NW waves per work-group, each wave owns 32 queries; two work-groups share a CU.
+template <int D, int NW>
+__global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
     const UnitDesc* __restrict__ descs, const AttnItem* __restrict__ items,
     const __bf16* __restrict__ q, const __bf16* __restrict__ k_cache,
     const __bf16* __restrict__ v_cache, int N_k, float scale,
     __bf16* __restrict__ out) {
   constexpr int KK = D / 16;        // MFMA steps over head_dim for S^T
   constexpr int MB = D / 32;        // 32-row blocks of O^T
-  constexpr int KS = D + kKPad;     // LDS row strides in elements
-  constexpr int VS = D + kVPad;
-  constexpr int QW = 32 * NQB;      // queries per wave
   constexpr int CPR = D / 8;        // 16-byte chunks per row
+  constexpr int RPI = 64 / CPR;     // tile rows covered by one wave-wide load instruction
+  constexpr int IPW = (kKT / RPI) / NW;  // load instructions per wave, tile and tensor
 
   const AttnItem it = items[blockIdx.x];
   if (it.desc < 0) return;
   const UnitDesc d = descs[it.desc];
   const int len = d.n_out;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
 
-  __shared__ __attribute__((aligned(16))) __bf16 Ks[kKT * KS];
-  __shared__ __attribute__((aligned(16))) __bf16 Vs[kKT * VS];
+  __shared__ __attribute__((aligned(1024))) __bf16 Ks[2][kKT * D];
+  __shared__ __attribute__((aligned(1024))) __bf16 Vs[2][kKT * D];
 
   // Q fragments (B operand of S^T = K Q^T): query col, head-dim slice [16kk + 8h, +8).
-  const int q0 = it.q_tile * (4 * QW) + w * QW;
-  bf16x8 qf[NQB][KK];
-#pragma unroll
-  for (int nb = 0; nb < NQB; ++nb) {
-    const int qi = min(q0 + nb * 32 + col, N_k - 1);
+  const int q0 = it.q_tile * (NW * 32) + w * 32;
+  bf16x8 qf[KK];
+  {
+    const int qi = min(q0 + col, N_k - 1);
     const __bf16* qrow = q + ((int64_t)d.unit * N_k + qi) * D;
 #pragma unroll
-    for (int kk = 0; kk < KK; ++kk)
-      qf[nb][kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * half);
+    for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * half);
   }
 
-  floatx16 o[NQB][MB];
+  floatx16 o[MB];
 #pragma unroll
-  for (int nb = 0; nb < NQB; ++nb)
+  for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) o[nb][mb][r] = 0.f;
-  float m_run[NQB], l_run[NQB];
-#pragma unroll
-  for (int nb = 0; nb < NQB; ++nb) {
-    m_run[nb] = -INFINITY;
-    l_run[nb] = 0.f;
-  }
+    for (int r = 0; r < 16; ++r) o[mb][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
   const float c2 = scale * kLog2eF;
 
-  const uint4* kg = reinterpret_cast<const uint4*>(k_cache + d.out_off * D);
-  const uint4* vg = reinterpret_cast<const uint4*>(v_cache + d.out_off * D);
+  const __bf16* kg = k_cache + d.out_off * D;
+  const __bf16* vg = v_cache + d.out_off * D;
 
-  for (int t0 = 0; t0 < len; t0 += kKT) {
-    __syncthreads();  // previous tile fully consumed
-    // ---- stage K/V tile (rows beyond len are zero) ----
+  // Rows past the end repeat the last valid row (finite data); their scores are
+  // masked to -inf below, so their probabilities are exactly 0.
+  auto issue = [&](int t0, int buf) {
 #pragma unroll
-    for (int e = tid; e < kKT * CPR; e += 256) {
-      const int r = e / CPR, ch = e % CPR;
-      uint4 kv = {0, 0, 0, 0}, vv = {0, 0, 0, 0};
-      if (t0 + r < len) {
-        kv = kg[(int64_t)(t0 + r) * CPR + ch];
-        vv = vg[(int64_t)(t0 + r) * CPR + ch];
-      }
-      *reinterpret_cast<uint4*>(&Ks[r * KS + ch * 8]) = kv;
-      *reinterpret_cast<uint4*>(&Vs[r * VS + ch * 8]) = vv;
+    for (int i = 0; i < IPW; ++i) {
+      const int ci = w + i * NW;                       // wave-uniform KiB index inside the tile
+      const int r = ci * RPI + lane / CPR, c = lane % CPR;
+      const int64_t grow = (int64_t)min(t0 + r, len - 1) * D;
+      load_to_lds(kg + grow + ((c ^ swz_k(r)) & (CPR - 1)) * 8, &Ks[buf][ci * 512]);
+      load_to_lds(vg + grow + ((c ^ swz_v(r)) & (CPR - 1)) * 8, &Vs[buf][ci * 512]);
     }
-    __syncthreads();
+  };
+
+  // per-lane LDS element offsets of the operand reads (tile-relative)
+  int k_off[KK];           // K operand: row col (+32 kb), chunk 2kk + half
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) k_off[kk] = col * D + (((2 * kk + half) ^ swz_k(col)) & (CPR - 1)) * 8;
+  const int g = lane >> 4, e = (lane >> 2) & 3, qd = lane & 3;
+  int v_off[MB];           // V^T operand: row 4 half + e (+16 sg, +32 kb, +8), head-dim 32mb + 16(g&1) + 4qd
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+    v_off[mb] = (4 * half + e) * D + (((4 * mb + 2 * (g & 1) + (qd >> 1)) ^ swz_v(e)) & (CPR - 1)) * 8 + 4 * (qd & 1);
+
+  const int n_tiles = (len + kKT - 1) / kKT;
+  issue(0, 0);
+  __syncthreads();
+
+  for (int t = 0; t < n_tiles; ++t) {
+    const int t0 = t * kKT;
+    const int buf = t & 1;
+    if (t + 1 < n_tiles) issue(t0 + kKT, buf ^ 1);   // lands while this tile is consumed
     const bool tail = (t0 + kKT > len);
+    const __bf16* Kt = Ks[buf];
+    const __bf16* Vt = Vs[buf];
 
 #pragma unroll
     for (int kb = 0; kb < kKT / 32; ++kb) {
-      // ---- S^T block: 32 keys x QW queries ----
-      floatx16 s[NQB];
+      if (t0 + kb * 32 >= len) break;  // whole block past the end (wave-uniform)
+      // ---- S^T block: 32 keys x 32 queries ----
+      floatx16 s;
 #pragma unroll
-      for (int nb = 0; nb < NQB; ++nb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) s[nb][r] = 0.f;
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Ks[(kb * 32 + col) * KS + 16 * kk + 8 * half]);
-#pragma unroll
-        for (int nb = 0; nb < NQB; ++nb)
-          s[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nb][kk], s[nb], 0, 0, 0);
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Kt[kb * 32 * D + k_off[kk]]);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
       }
       if (tail) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int key = t0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-          if (key >= len) {
-#pragma unroll
-            for (int nb = 0; nb < NQB; ++nb) s[nb][r] = -INFINITY;
-          }
+          if (key >= len) s[r] = -INFINITY;
         }
       }
       // ---- online softmax (per lane: one query, 16 keys; partner lane^32 has the other 16) ----
-      bf16x8 pf[NQB][2];
+      float mx = s[0];
 #pragma unroll
-      for (int nb = 0; nb < NQB; ++nb) {
-        float mx = s[nb][0];
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float m_new = fmaxf(m_run, mx);   // finite: the block holds a valid key
+      const float mc = m_new * c2;
+      float psum = 0.f;
+      bf16x8 pf[2];
 #pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[nb][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run[nb], mx);   // finite: key 0 of the tile is valid
-        const float mc = m_new * c2;
-        float psum = 0.f;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const float p = __builtin_amdgcn_exp2f(fmaf(s[nb][r], c2, -mc));
-          psum += p;
-          pf[nb][r >> 3][r & 7] = (__bf16)p;
-        }
-        if (__any(m_new > m_run[nb])) {
-          const float a = __builtin_amdgcn_exp2f((m_run[nb] - m_new) * c2);
-          l_run[nb] *= a;
-#pragma unroll
-          for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[nb][mb][r] *= a;
-        }
-        l_run[nb] += psum;
-        m_run[nb] = m_new;
+      for (int r = 0; r < 16; ++r) {
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -mc));
+        psum += p;
+        pf[r >> 3][r & 7] = (__bf16)p;
       }
+      if (__any(m_new > m_run)) {
+        const float a = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+        l_run *= a;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[mb][r] *= a;
+      }
+      l_run += psum;
+      m_run = m_new;
       // ---- O^T += V^T P^T ----
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
         for (int sg = 0; sg < 2; ++sg) {
-          // lanes 4e+qd of a 16-lane group address key (16sg + 4h + e), head-dim 32mb + 16(g&1) + 4qd
-          const int g = lane >> 4, e = (lane >> 2) & 3, qd = lane & 3;
-          const __bf16* vp =
-              &Vs[(kb * 32 + 16 * sg + 4 * half + e) * VS + 32 * mb + 16 * (g & 1) + 4 * qd];
+          const __bf16* vp = &Vt[(kb * 32 + 16 * sg) * D + v_off[mb]];
           const bf16x4 v0 = lds_read_tr(vp);
-          const bf16x4 v1 = lds_read_tr(vp + 8 * VS);
+          const bf16x4 v1 = lds_read_tr(vp + 8 * D);
           bf16x8 vf;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             vf[i] = v0[i];
             vf[4 + i] = v1[i];
           }
-#pragma unroll
-          for (int nb = 0; nb < NQB; ++nb)
-            o[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nb][sg], o[nb][mb], 0, 0, 0);
+          o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sg], o[mb], 0, 0, 0);
         }
       }
     }
+    __syncthreads();  // next tile has landed for every wave; this tile is free to overwrite
   }
 
   // ---- normalise and store: lane holds query col, head-dim rows 32mb + 8(r/4) + 4h + r%4 ----
+  const float l = l_run + __shfl_xor(l_run, 32, 64);
+  const float inv = 1.f / l;
+  const int qi = q0 + col;
+  if (qi < N_k) {
+    __bf16* orow = out + ((int64_t)d.unit * N_k + qi) * D;
 #pragma unroll
-  for (int nb = 0; nb < NQB; ++nb) {
-    const float l = l_run[nb] + __shfl_xor(l_run[nb], 32, 64);
-    const float inv = 1.f / l;
-    const int qi = q0 + nb * 32 + col;
-    if (qi < N_k) {
-      __bf16* orow = out + ((int64_t)d.unit * N_k + qi) * D;
+    for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 pk;
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-          bf16x4 pk;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) pk[i] = (__bf16)(o[nb][mb][4 * r4 + i] * inv);
-          *reinterpret_cast<bf16x4*>(orow + 32 * mb + 8 * r4 + 4 * half) = pk;
-        }
+        for (int i = 0; i < 4; ++i) pk[i] = (__bf16)(o[mb][4 * r4 + i] * inv);
+        *reinterpret_cast<bf16x4*>(orow + 32 * mb + 8 * r4 + 4 * half) = pk;
       }
     }
   }
@@ -277,9 +284,19 @@ __global__ __launch_bounds__(256) void attn_mfma(
 
 }  // namespace
 
-int attn_q_tile_rows(int dtype, int head_dim) {
-  (void)head_dim;
-  return dtype == 1 ? kGenQ : 4 * 32 * 1;
+// Queries per work item.
+int attn_q_tile_rows(int dtype, int head_dim, int n_units, int N_k) {
+  (void)head_dim; (void)n_units; (void)N_k;
+  return dtype == 1 ? kGenQ : 128;
+}
+
+template <int D, int NW>
+static void launch_mfma_t(hipStream_t s, const UnitDesc* descs, const AttnItem* items, int n_items,
+                          const void* q, const void* k_cache, const void* v_cache, int N_k,
+                          float scale, void* out) {
+  typedef __bf16 T;
+  hipLaunchKernelGGL((attn_mfma<D, NW>), dim3(n_items), dim3(64 * NW), 0, s, descs, items,
+                     (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out);
 }
 
 void launch_attn(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, const AttnItem* items,
@@ -296,15 +313,10 @@ void launch_attn(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, 
       hipLaunchKernelGGL((attn_generic<float, 128>), dim3(n_items), dim3(kGenQ), 0, s, descs, items,
                          (const float*)q, (const float*)k_cache, (const float*)v_cache, N_k, scale,
                          (float*)out);
-  } else {
-    typedef __bf16 T;
-    if (head_dim == 64)
-      hipLaunchKernelGGL((attn_mfma<64, 1>), dim3(n_items), dim3(256), 0, s, descs, items,
-                         (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out);
-    else
-      hipLaunchKernelGGL((attn_mfma<128, 1>), dim3(n_items), dim3(256), 0, s, descs, items,
-                         (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out);
+    return;
   }
+  if (head_dim == 64) launch_mfma_t<64, 4>(s, descs, items, n_items, q, k_cache, v_cache, N_k, scale, out);
+  else launch_mfma_t<128, 4>(s, descs, items, n_items, q, k_cache, v_cache, N_k, scale, out);
 }
 
 }  // namespace hack

@@ -9,7 +9,7 @@ namespace hack {
 namespace {
 
 constexpr int kThreads = 256;
-constexpr int kRowsInFlight = 4;  // independent row copies per lane group
+constexpr int kRowsInFlight = 8;  // independent row copies per lane group
 
 // LPR = 16-byte lanes per row (row_bytes / 16).
 template <int LPR>
@@ -35,41 +35,39 @@ __global__ __launch_bounds__(kThreads) void move_kernel(
   const int32_t* idx = kept_idx ? kept_idx + (int64_t)d.unit * idx_stride : nullptr;
   const bool with_pos = (out.pos != nullptr);
 
-  uint4 kr[kRowsInFlight], vr[kRowsInFlight];
-  int32_t pr[kRowsInFlight];
-  int64_t dst[kRowsInFlight];
+  // Phase 1: source row of every in-flight copy (one dependent index load each),
+  // clamped to a valid row so that phase 2 can load without branches.
+  int s[kRowsInFlight];
+  bool live[kRowsInFlight];
 #pragma unroll
   for (int r = 0; r < kRowsInFlight; ++r) {
     const int i = row0 + r * GROUPS + g;
-    dst[r] = -1;
-    if (i < n_rows) {
-      int s;  // source row in the virtual concatenation
-      if (d.mode == MOVE_APPEND) {
-        s = d.len_in + i;
-        dst[r] = d.in_off + d.len_in + i;
-      } else {
-        s = idx[i];
-        dst[r] = d.out_off + i;
-      }
-      if (s < d.len_in) {
-        const int64_t src = d.in_off + s;
-        kr[r] = kin[src * LPR + lane];
-        vr[r] = vin[src * LPR + lane];
-        pr[r] = (with_pos && in.pos) ? in.pos[src] : 0;
-      } else {
-        const int64_t src = new_base + (s - d.len_in);
-        kr[r] = k_new[src * LPR + lane];
-        vr[r] = v_new[src * LPR + lane];
-        pr[r] = pos_new + (s - d.len_in);
-      }
-    }
+    live[r] = i < n_rows;
+    const int ic = live[r] ? i : n_rows - 1;
+    s[r] = (d.mode == MOVE_APPEND) ? d.len_in + ic : idx[ic];
   }
+  // Phase 2: all loads in flight before the first store.
+  uint4 kr[kRowsInFlight], vr[kRowsInFlight];
+  int32_t pr[kRowsInFlight];
 #pragma unroll
   for (int r = 0; r < kRowsInFlight; ++r) {
-    if (dst[r] >= 0) {
-      kout[dst[r] * LPR + lane] = kr[r];
-      vout[dst[r] * LPR + lane] = vr[r];
-      if (with_pos && lane == 0) out.pos[dst[r]] = pr[r];
+    const bool from_cache = s[r] < d.len_in;
+    const int64_t src = from_cache ? d.in_off + s[r] : new_base + (s[r] - d.len_in);
+    const uint4* kp = from_cache ? kin : k_new;
+    const uint4* vp = from_cache ? vin : v_new;
+    kr[r] = kp[src * LPR + lane];
+    vr[r] = vp[src * LPR + lane];
+    pr[r] = pos_new + (s[r] - d.len_in);
+    if (with_pos && from_cache && in.pos) pr[r] = in.pos[src];
+  }
+  const int64_t dst0 = (d.mode == MOVE_APPEND) ? d.in_off + d.len_in : d.out_off;
+#pragma unroll
+  for (int r = 0; r < kRowsInFlight; ++r) {
+    if (live[r]) {
+      const int64_t dst = dst0 + row0 + r * GROUPS + g;
+      kout[dst * LPR + lane] = kr[r];
+      vout[dst * LPR + lane] = vr[r];
+      if (with_pos && lane == 0) out.pos[dst] = pr[r];
     }
   }
 }

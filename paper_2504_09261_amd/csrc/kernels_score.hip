@@ -33,15 +33,38 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 constexpr int kThreads = 256;
 constexpr double kLog2e = 1.4426950408889634074;
 
-// exp(x) for x <= 0 with ~1 ulp float32 accuracy in a double result: the range
-// reduction is done in fp64 so a large |x| does not cost relative accuracy.
-__device__ __forceinline__ double exp_neg(double x) {
-  const double t = x * kLog2e;
+// 2^t for a double t with ~1 ulp float32 accuracy: the range reduction is done
+// in fp64 so a large |t| does not cost relative accuracy; the result is a float
+// (ldexp of the float mantissa part is exact).
+__device__ __forceinline__ float exp2_split(double t) {
   const double n = rint(t);
   const float r = (float)(t - n);  // |r| <= 0.5
-  const float e = __builtin_amdgcn_exp2f(r);
-  const int ni = (n < -1100.0) ? -1100 : (int)n;
-  return ldexp((double)e, ni);
+  return ldexpf(__builtin_amdgcn_exp2f(r), (int)n);
+}
+__device__ __forceinline__ double exp_neg(double x) { return (double)exp2_split(x * kLog2e); }
+
+// All-reduce over the 32 lanes of a half-wave without touching LDS memory:
+// two quad permutes, the two row mirrors, then a swizzle across the 16-lane rows.
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float swz_xor16(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));
+}
+__device__ __forceinline__ float half_max(float v) {
+  v = fmaxf(v, dpp_mov<0xB1>(v));
+  v = fmaxf(v, dpp_mov<0x4E>(v));
+  v = fmaxf(v, dpp_mov<0x141>(v));
+  v = fmaxf(v, dpp_mov<0x140>(v));
+  return fmaxf(v, swz_xor16(v));
+}
+__device__ __forceinline__ float half_sum(float v) {
+  v += dpp_mov<0xB1>(v);
+  v += dpp_mov<0x4E>(v);
+  v += dpp_mov<0x141>(v);
+  v += dpp_mov<0x140>(v);
+  return v + swz_xor16(v);
 }
 
 __device__ __forceinline__ float to_float(float v) { return v; }
@@ -56,6 +79,8 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int m) {
 
 // Combine the per-chunk (max, sum) partials of one unit: rows i < n_obs handled
 // by threads i < 32; result in sm[i] (max) and sinv[i] (1 / normaliser).
+// LOG2: the partials are in log2 units (MFMA path) instead of natural units.
+template <bool LOG2>
 __device__ __forceinline__ void combine_stats(const double* __restrict__ st, int n_chunks, int n_obs,
                                               double* sm, double* sinv) {
   const int i = threadIdx.x;
@@ -65,7 +90,7 @@ __device__ __forceinline__ void combine_stats(const double* __restrict__ st, int
       for (int c = 0; c < n_chunks; ++c) m = fmax(m, st[(c * kMaxObs + i) * 2]);
       for (int c = 0; c < n_chunks; ++c) {
         const double mc = st[(c * kMaxObs + i) * 2], lc = st[(c * kMaxObs + i) * 2 + 1];
-        l += lc * exp_neg(mc - m);
+        l += lc * (LOG2 ? (double)exp2_split(mc - m) : exp_neg(mc - m));
       }
     }
     sm[i] = (i < n_obs) ? m : 0.0;  // unused rows: finite shift, zero weight
@@ -98,7 +123,7 @@ __global__ __launch_bounds__(kThreads) void score_generic(
     qs[i][c] = to_float(q[((int64_t)d.unit * N_k + q_rows[i]) * D + c]);
   }
   double* st_unit = stats + (int64_t)blockIdx.y * max_chunks * kMaxObs * 2;
-  if (PASS == 2) combine_stats(st_unit, n_chunks, n_obs, sm, sinv);
+  if (PASS == 2) combine_stats<false>(st_unit, n_chunks, n_obs, sm, sinv);
   __syncthreads();
 
   const int j = key0 + tid;
@@ -173,7 +198,7 @@ __global__ __launch_bounds__(kThreads) void score_mfma(
   const int col = lane & 31, half = lane >> 5;
 
   __shared__ double sm[kMaxObs], sinv[kMaxObs];
-  __shared__ double redm[4][kMaxObs], redl[4][kMaxObs];
+  __shared__ float redm[4][kMaxObs], redl[4][kMaxObs];
   double* st_unit = stats + (int64_t)blockIdx.y * max_chunks * kMaxObs * 2;
 
   // K fragments of this wave's tiles: issue every load before anything else.
@@ -202,11 +227,11 @@ __global__ __launch_bounds__(kThreads) void score_mfma(
       qf[kk] = qv ? *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * half) : z;
     }
   }
-  if (PASS == 2) combine_stats(st_unit, n_chunks, n_obs, sm, sinv);
+  if (PASS == 2) combine_stats<true>(st_unit, n_chunks, n_obs, sm, sinv);
 
-  // Logits: every MFMA covers 16 head-dim elements and starts from a zero
-  // accumulator; the per-step partials are summed in fp64, so the only float32
-  // rounding is on partial sums that are small next to the full dot product.
+  // Raw dot products: every MFMA covers 16 head-dim elements and starts from a
+  // zero accumulator; the slice results are summed in fp64, so float32 rounding
+  // only ever acts on partial sums that are small next to the full dot product.
   double sd[TPW][16];
 #pragma unroll
   for (int t = 0; t < TPW; ++t) {
@@ -214,45 +239,40 @@ __global__ __launch_bounds__(kThreads) void score_mfma(
     for (int r = 0; r < 16; ++r) sd[t][r] = 0.0;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
-      floatx16 z = {0};
-      const floatx16 c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], kf[t][kk], z, 0, 0, 0);
+      floatx16 c = {0};
+      c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], kf[t][kk], c, 0, 0, 0);
 #pragma unroll
       for (int r = 0; r < 16; ++r) sd[t][r] += (double)c[r];
     }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) sd[t][r] *= (double)scale;
   }
+  const double c2 = (double)scale * kLog2e;  // logits in log2 units: t = dot * c2
 
   if (PASS == 1) {
-    // chunk reference per query row (a float32 value at or just below the max):
-    // in-lane over tiles, then over the 32 key lanes of the half-wave
+    // Per query row a float32 reference near the chunk maximum (any common value
+    // works: it only keeps the exponentials in range), then the sum of 2^(t - ref).
     float mrow[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       float m = -INFINITY;
 #pragma unroll
       for (int t = 0; t < TPW; ++t) m = fmaxf(m, valid[t] ? (float)sd[t][r] : -INFINITY);
-#pragma unroll
-      for (int o = 1; o < 32; o <<= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-      mrow[r] = m;
+      mrow[r] = half_max(m);
     }
     if (col == 0) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) redm[w][c_row(r, half)] = (double)mrow[r];
+      for (int r = 0; r < 16; ++r) redm[w][c_row(r, half)] = mrow[r];
     }
     __syncthreads();
-    double lrow[16];
+    float lrow[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int i = c_row(r, half);
-      const double m = fmax(fmax(redm[0][i], redm[1][i]), fmax(redm[2][i], redm[3][i]));
-      double l = 0.0;
+      const double ref = (double)fmaxf(fmaxf(redm[0][i], redm[1][i]), fmaxf(redm[2][i], redm[3][i])) * c2;
+      float l = 0.f;
 #pragma unroll
       for (int t = 0; t < TPW; ++t)
-        if (valid[t]) l += exp_neg(sd[t][r] - m);
-#pragma unroll
-      for (int o = 1; o < 32; o <<= 1) l += shfl_xor_f64(l, o);
-      lrow[r] = l;
+        if (valid[t]) l += exp2_split(fma(sd[t][r], c2, -ref));
+      lrow[r] = half_sum(l);
     }
     if (col == 0) {
 #pragma unroll
@@ -262,8 +282,8 @@ __global__ __launch_bounds__(kThreads) void score_mfma(
     if (tid < kMaxObs) {
       const int i = tid;
       double* o2 = st_unit + ((int64_t)blockIdx.x * kMaxObs + i) * 2;
-      o2[0] = fmax(fmax(redm[0][i], redm[1][i]), fmax(redm[2][i], redm[3][i]));
-      o2[1] = redl[0][i] + redl[1][i] + redl[2][i] + redl[3][i];
+      o2[0] = (double)fmaxf(fmaxf(redm[0][i], redm[1][i]), fmaxf(redm[2][i], redm[3][i])) * c2;
+      o2[1] = ((double)redl[0][i] + (double)redl[1][i]) + ((double)redl[2][i] + (double)redl[3][i]);
     }
   } else {
     __syncthreads();  // sm / sinv ready
@@ -278,7 +298,7 @@ __global__ __launch_bounds__(kThreads) void score_mfma(
     for (int t = 0; t < TPW; ++t) {
       double imp = 0.0;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) imp += exp_neg(sd[t][r] - m_i[r]) * inv_i[r];
+      for (int r = 0; r < 16; ++r) imp = fma((double)exp2_split(fma(sd[t][r], c2, -m_i[r])), inv_i[r], imp);
       imp += shfl_xor_f64(imp, 32);
       const int j = key0 + (w * TPW + t) * 32 + col;
       if (valid[t] && half == 0) importance[(int64_t)d.unit * imp_stride + j] = (float)imp;
