@@ -107,15 +107,43 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
 // K/V tiles go from HBM straight into LDS (global_load_lds, 16 B per lane, one
 // contiguous KiB per wave instruction), so LDS rows cannot be padded; bank
 // conflicts are avoided by a swizzle instead: the 16-byte chunk at position c of
-// LDS row r holds global chunk c ^ f(r), with f_K(r) = r & 7 (b128 operand reads
-// walk 8 consecutive rows) and f_V(r) = 2 (r & 3) (transposing reads walk 4
-// consecutive rows, 32 bytes each).
-__device__ __forceinline__ int swz_k(int r) { return r & 7; }
-__device__ __forceinline__ int swz_v(int r) { return 2 * (r & 3); }
+// LDS row r holds global chunk c ^ f(r).  The LDS moves 256 bytes per clock (64
+// banks of 4 bytes), so one phase of a b128 read covers 16 consecutive lanes (16
+// key rows at one chunk position) and one phase of a transposing b64 read covers
+// 32 lanes (4 key rows x 64 bytes); f spreads those over all 16 chunk slots of
+// 256 bytes:  D=128 (256-byte rows): f_K(r) = r & 15,        f_V(r) = 4 (r & 3)
+//             D=64  (128-byte rows): f_K(r) = (r >> 1) & 7,  f_V(r) = 4 ((r >> 1) & 1)
+// (measured: SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE was exactly 0.5 with the
+// 32-bank variants r & 7 and 2 (r & 3)).
+template <int D> __device__ __forceinline__ int swz_k(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
+template <int D> __device__ __forceinline__ int swz_v(int r) { return D == 128 ? 4 * (r & 3) : 4 * ((r >> 1) & 1); }
 
-__device__ __forceinline__ void load_to_lds(const __bf16* src, __bf16* lds_wave_base) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+// The copy is issued from inline assembly so that the compiler does not wait for
+// it before unrelated LDS reads (it would otherwise drain every outstanding LDS
+// write of this kind before the next ds_read, which serialises load and
+// compute).  The matching wait is dma_wait_all(), placed by hand before the
+// barrier that publishes the tile.  lds_addr is the wave-uniform LDS byte
+// address of the KiB this wave instruction fills (lane l writes bytes [16l, 16l+16)).
+__device__ __forceinline__ void load_to_lds(const __bf16* src, const __bf16* lds_wave_base) {
+  const unsigned lds_addr = (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)lds_wave_base;
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :: "v"(src), "s"(lds_addr) : "memory", "m0");
+}
+__device__ __forceinline__ void dma_wait_all() {
+  __builtin_amdgcn_sched_barrier(0);  // keep the tile's compute above the wait
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// max / sum over the lane pair (l, l ^ 32) with one VALU swap instead of an LDS permute
+__device__ __forceinline__ float pair_max(float v) {
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__builtin_bit_cast(float, (unsigned)r[0]), __builtin_bit_cast(float, (unsigned)r[1]));
+}
+__device__ __forceinline__ float pair_sum(float v) {
+  const unsigned u = __builtin_bit_cast(unsigned, v);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
 }
 
 // NW waves per work-group, each wave owns 32 queries; two work-groups share a CU.
@@ -150,6 +178,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
     const __bf16* qrow = q + ((int64_t)d.unit * N_k + qi) * D;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * half);
+    // Consume the fragments here so that their loads are waited for before the
+    // main loop: a vmcnt wait inside the loop would also drain the tile copies
+    // that are meant to stay in flight.
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) asm volatile("" ::"v"(qf[kk]));
   }
 
   floatx16 o[MB];
@@ -171,23 +204,24 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
       const int ci = w + i * NW;                       // wave-uniform KiB index inside the tile
       const int r = ci * RPI + lane / CPR, c = lane % CPR;
       const int64_t grow = (int64_t)min(t0 + r, len - 1) * D;
-      load_to_lds(kg + grow + ((c ^ swz_k(r)) & (CPR - 1)) * 8, &Ks[buf][ci * 512]);
-      load_to_lds(vg + grow + ((c ^ swz_v(r)) & (CPR - 1)) * 8, &Vs[buf][ci * 512]);
+      load_to_lds(kg + grow + ((c ^ swz_k<D>(r)) & (CPR - 1)) * 8, &Ks[buf][ci * 512]);
+      load_to_lds(vg + grow + ((c ^ swz_v<D>(r)) & (CPR - 1)) * 8, &Vs[buf][ci * 512]);
     }
   };
 
   // per-lane LDS element offsets of the operand reads (tile-relative)
   int k_off[KK];           // K operand: row col (+32 kb), chunk 2kk + half
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) k_off[kk] = col * D + (((2 * kk + half) ^ swz_k(col)) & (CPR - 1)) * 8;
+  for (int kk = 0; kk < KK; ++kk) k_off[kk] = col * D + (((2 * kk + half) ^ swz_k<D>(col)) & (CPR - 1)) * 8;
   const int g = lane >> 4, e = (lane >> 2) & 3, qd = lane & 3;
   int v_off[MB];           // V^T operand: row 4 half + e (+16 sg, +32 kb, +8), head-dim 32mb + 16(g&1) + 4qd
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
-    v_off[mb] = (4 * half + e) * D + (((4 * mb + 2 * (g & 1) + (qd >> 1)) ^ swz_v(e)) & (CPR - 1)) * 8 + 4 * (qd & 1);
+    v_off[mb] = (4 * half + e) * D + (((4 * mb + 2 * (g & 1) + (qd >> 1)) ^ swz_v<D>(e)) & (CPR - 1)) * 8 + 4 * (qd & 1);
 
   const int n_tiles = (len + kKT - 1) / kKT;
   issue(0, 0);
+  dma_wait_all();
   __syncthreads();
 
   for (int t = 0; t < n_tiles; ++t) {
@@ -221,7 +255,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
       float mx = s[0];
 #pragma unroll
       for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = pair_max(mx);
       const float m_new = fmaxf(m_run, mx);   // finite: the block holds a valid key
       const float mc = m_new * c2;
       float psum = 0.f;
@@ -260,11 +294,12 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
         }
       }
     }
+    dma_wait_all();
     __syncthreads();  // next tile has landed for every wave; this tile is free to overwrite
   }
 
   // ---- normalise and store: lane holds query col, head-dim rows 32mb + 8(r/4) + 4h + r%4 ----
-  const float l = l_run + __shfl_xor(l_run, 32, 64);
+  const float l = pair_sum(l_run);
   const float inv = 1.f / l;
   const int qi = q0 + col;
   if (qi < N_k) {
