@@ -18,6 +18,8 @@
 //     the b128 K reads and the transposing V reads bank-conflict free.
 // fp32 path: one query per lane, fp32 FMA, K/V rows broadcast from LDS; exact
 // enough for the 1e-4 bar and only used for the small fp32 configuration.
+#include <type_traits>
+
 #include "hack_internal.h"
 
 namespace hack {
@@ -26,6 +28,7 @@ namespace {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
 
@@ -97,6 +100,7 @@ __global__ __launch_bounds__(kGenQ) void attn_generic(
 // bf16 MFMA path
 // ---------------------------------------------------------------------------
 constexpr int kKT = 64;      // keys per LDS tile
+constexpr float kRescaleAbove = 65536.f;  // a block sum of probabilities at or above this moves the reference
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
   shortx4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -114,7 +118,7 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
 // 256 bytes:  D=128 (256-byte rows): f_K(r) = r & 15,        f_V(r) = 4 (r & 3)
 //             D=64  (128-byte rows): f_K(r) = (r >> 1) & 7,  f_V(r) = 4 ((r >> 1) & 1)
 // (measured: SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE was exactly 0.5 with the
-// 32-bank variants r & 7 and 2 (r & 3)).
+// 32-bank variants r & 7 and 2 (r & 3), and is 0 with these).
 template <int D> __device__ __forceinline__ int swz_k(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
 template <int D> __device__ __forceinline__ int swz_v(int r) { return D == 128 ? 4 * (r & 3) : 4 * ((r >> 1) & 1); }
 
@@ -122,19 +126,22 @@ template <int D> __device__ __forceinline__ int swz_v(int r) { return D == 128 ?
 // it before unrelated LDS reads (it would otherwise drain every outstanding LDS
 // write of this kind before the next ds_read, which serialises load and
 // compute).  The matching wait is dma_wait_all(), placed by hand before the
-// barrier that publishes the tile.  lds_addr is the wave-uniform LDS byte
-// address of the KiB this wave instruction fills (lane l writes bytes [16l, 16l+16)).
-__device__ __forceinline__ void load_to_lds(const __bf16* src, const __bf16* lds_wave_base) {
-  const unsigned lds_addr = (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)lds_wave_base;
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(src), "s"(lds_addr) : "memory", "m0");
+// barrier that publishes the tile.  base: wave-uniform global address of the
+// tile; voff: this lane's byte offset inside the tile; lds_addr: wave-uniform LDS
+// byte address of the KiB this instruction fills (lane l writes bytes [16l, 16l+16)).
+__device__ __forceinline__ void load_to_lds(const __bf16* base, unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :: "v"(voff), "s"(base), "s"(lds_addr) : "memory", "m0");
 }
 __device__ __forceinline__ void dma_wait_all() {
   __builtin_amdgcn_sched_barrier(0);  // keep the tile's compute above the wait
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }
+__device__ __forceinline__ unsigned lds_addr_of(const void* p) {
+  return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
 
-// max / sum over the lane pair (l, l ^ 32) with one VALU swap instead of an LDS permute
+// max over the lane pair (l, l ^ 32) with one VALU swap instead of an LDS permute
 __device__ __forceinline__ float pair_max(float v) {
   const unsigned u = __builtin_bit_cast(unsigned, v);
   const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
@@ -147,6 +154,16 @@ __device__ __forceinline__ float pair_sum(float v) {
 }
 
 // NW waves per work-group, each wave owns 32 queries; two work-groups share a CU.
+//
+// The vector ALU is the scarce unit here (per 32-key block a wave issues 16 MFMAs
+// but also has to exponentiate 16 scores per lane), so the softmax is kept to
+// fma + exp2 + bf16 pack + a bf16 dot2 for the row sum:
+//   * the running reference m_run is only moved when a probability would leave
+//     [0, 2^16): the exponentials are formed optimistically against the current
+//     reference, and only if some lane's block sum says "too large" (or inf, as
+//     in the very first block) is the max computed and everything rescaled;
+//   * the row sum is taken over the bf16-rounded probabilities, the same numbers
+//     the PV product uses.
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
     const UnitDesc* __restrict__ descs, const AttnItem* __restrict__ items,
@@ -158,6 +175,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
   constexpr int CPR = D / 8;        // 16-byte chunks per row
   constexpr int RPI = 64 / CPR;     // tile rows covered by one wave-wide load instruction
   constexpr int IPW = (kKT / RPI) / NW;  // load instructions per wave, tile and tensor
+  constexpr int TILE_ELEMS = kKT * D;
 
   const AttnItem it = items[blockIdx.x];
   if (it.desc < 0) return;
@@ -167,8 +185,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
 
-  __shared__ __attribute__((aligned(1024))) __bf16 Ks[2][kKT * D];
-  __shared__ __attribute__((aligned(1024))) __bf16 Vs[2][kKT * D];
+  __shared__ __attribute__((aligned(1024))) __bf16 Ks[2][TILE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) __bf16 Vs[2][TILE_ELEMS];
 
   // Q fragments (B operand of S^T = K Q^T): query col, head-dim slice [16kk + 8h, +8).
   const int q0 = it.q_tile * (NW * 32) + w * 32;
@@ -192,24 +210,52 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
     for (int r = 0; r < 16; ++r) o[mb][r] = 0.f;
   float m_run = -INFINITY, l_run = 0.f;
   const float c2 = scale * kLog2eF;
+  float mc = -INFINITY;   // m_run * c2
 
   const __bf16* kg = k_cache + d.out_off * D;
   const __bf16* vg = v_cache + d.out_off * D;
 
-  // Rows past the end repeat the last valid row (finite data); their scores are
-  // masked to -inf below, so their probabilities are exactly 0.
-  auto issue = [&](int t0, int buf) {
+  // Tile copies.  Lane l of load instruction i of this wave fills LDS row
+  // r = (w + i NW) RPI + l / CPR, chunk position c = l % CPR, from global chunk
+  // c ^ f(r) of tile row r; the byte offsets inside a full tile are loop invariant.
+  unsigned k_src[IPW], v_src[IPW];
+#pragma unroll
+  for (int i = 0; i < IPW; ++i) {
+    const int r = (w + i * NW) * RPI + lane / CPR, c = lane % CPR;
+    k_src[i] = (unsigned)(r * D + ((c ^ swz_k<D>(r)) & (CPR - 1)) * 8) * 2u;
+    v_src[i] = (unsigned)(r * D + ((c ^ swz_v<D>(r)) & (CPR - 1)) * 8) * 2u;
+  }
+  const unsigned ks_lds = lds_addr_of(&Ks[0][0]), vs_lds = lds_addr_of(&Vs[0][0]);
+  auto issue_full = [&](int t0, int buf) {
+    const __bf16* kb = kg + (int64_t)t0 * D;
+    const __bf16* vb = vg + (int64_t)t0 * D;
 #pragma unroll
     for (int i = 0; i < IPW; ++i) {
-      const int ci = w + i * NW;                       // wave-uniform KiB index inside the tile
-      const int r = ci * RPI + lane / CPR, c = lane % CPR;
-      const int64_t grow = (int64_t)min(t0 + r, len - 1) * D;
-      load_to_lds(kg + grow + ((c ^ swz_k<D>(r)) & (CPR - 1)) * 8, &Ks[buf][ci * 512]);
-      load_to_lds(vg + grow + ((c ^ swz_v<D>(r)) & (CPR - 1)) * 8, &Vs[buf][ci * 512]);
+      const unsigned dst = (unsigned)((buf * TILE_ELEMS + (w + i * NW) * 512) * 2);
+      load_to_lds(kb, k_src[i], ks_lds + dst);
+      load_to_lds(vb, v_src[i], vs_lds + dst);
     }
   };
-
-  // per-lane LDS element offsets of the operand reads (tile-relative)
+  // Ragged last tile: rows past the end repeat the last valid row (finite data);
+  // their scores are masked to -inf, so their probabilities are exactly 0.
+  auto issue_tail = [&](int t0, int buf) {
+    const __bf16* kb = kg + (int64_t)t0 * D;
+    const __bf16* vb = vg + (int64_t)t0 * D;
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) {
+      const int r = (w + i * NW) * RPI + lane / CPR, c = lane % CPR;
+      const int rc = min(r, len - 1 - t0);
+      const unsigned dst = (unsigned)((buf * TILE_ELEMS + (w + i * NW) * 512) * 2);
+      load_to_lds(kb, (unsigned)(rc * D + ((c ^ swz_k<D>(r)) & (CPR - 1)) * 8) * 2u, ks_lds + dst);
+      load_to_lds(vb, (unsigned)(rc * D + ((c ^ swz_v<D>(r)) & (CPR - 1)) * 8) * 2u, vs_lds + dst);
+    }
+  };
+  auto issue = [&](int t0, int buf) {
+    if (t0 + kKT <= len) issue_full(t0, buf);
+    else issue_tail(t0, buf);
+  };
+  // per-lane LDS element offsets of the operand reads (tile-relative); everything
+  // else in an LDS address is a compile-time immediate (buffer, key block, sg)
   int k_off[KK];           // K operand: row col (+32 kb), chunk 2kk + half
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) k_off[kk] = col * D + (((2 * kk + half) ^ swz_k<D>(col)) & (CPR - 1)) * 8;
@@ -219,83 +265,118 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
   for (int mb = 0; mb < MB; ++mb)
     v_off[mb] = (4 * half + e) * D + (((4 * mb + 2 * (g & 1) + (qd >> 1)) ^ swz_v<D>(e)) & (CPR - 1)) * 8 + 4 * (qd & 1);
 
+  const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
+
+  // One 32-key block of the tile in buffer BUF: S^T, softmax, O^T update.
+  auto block = [&](auto buf_tag, auto kb_tag, auto tail_tag, int t0) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    constexpr int KB = decltype(kb_tag)::value;
+    const __bf16* Kt = &Ks[BUF][KB * 32 * D];
+    const __bf16* Vt = &Vs[BUF][KB * 32 * D];
+    // ---- S^T block: 32 keys x 32 queries ----
+    floatx16 sc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sc[r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Kt[k_off[kk]]);
+      sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sc, 0, 0, 0);
+    }
+    if (decltype(tail_tag)::value) {   // ragged end: keys past the end get -inf
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = t0 + KB * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (key >= len) sc[r] = -INFINITY;
+      }
+    }
+    // ---- probabilities against the current reference (per lane: one query, 16
+    //      keys; the partner lane l ^ 32 holds the other 16) ----
+    bf16x8 pf[2];
+    float psum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) pf[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[r], c2, -mc));
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      const bf16x2 pr = {pf[r >> 3][r & 7], pf[r >> 3][(r & 7) + 1]};
+      psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, psum, false);
+    }
+    if (__any(!(psum < kRescaleAbove))) {
+      // Some probability left the safe range (always so in the first block, where
+      // the reference is -inf): move the reference to the running max, bring the
+      // accumulators to the new scale and redo this block's probabilities.
+      float mx = sc[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
+      mx = pair_max(mx);
+      const float m_new = fmaxf(m_run, mx);   // finite: the block holds a valid key
+      const float a = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+      l_run *= a;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[mb][r] *= a;
+      m_run = m_new;
+      mc = m_new * c2;
+      psum = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) pf[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[r], c2, -mc));
+#pragma unroll
+      for (int r = 0; r < 16; r += 2) {
+        const bf16x2 pr = {pf[r >> 3][r & 7], pf[r >> 3][(r & 7) + 1]};
+        psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, psum, false);
+      }
+    }
+    l_run += psum;
+    // ---- O^T += V^T P^T ----
+#pragma unroll
+    for (int sg = 0; sg < 2; ++sg) {
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        const __bf16* vp = &Vt[16 * sg * D + v_off[mb]];
+        const bf16x4 v0 = lds_read_tr(vp);
+        const bf16x4 v1 = lds_read_tr(vp + 8 * D);
+        bf16x8 vf;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          vf[i] = v0[i];
+          vf[4 + i] = v1[i];
+        }
+        o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sg], o[mb], 0, 0, 0);
+      }
+    }
+  };
+
+  using K0 = std::integral_constant<int, 0>;
+  using K1 = std::integral_constant<int, 1>;
+  using B0 = std::integral_constant<int, 0>;
+  using B1 = std::integral_constant<int, 1>;
   const int n_tiles = (len + kKT - 1) / kKT;
+  const int n_full = len / kKT;       // tiles without a ragged end
+  // One tile: start the copy of the next one, consume this one, publish the next.
+  auto tile = [&](auto buf_tag, auto tail_tag, int t) {
+    constexpr int BUF = decltype(buf_tag)::value;
+    constexpr bool TAIL = decltype(tail_tag)::value;
+    const int t0 = t * kKT;
+    if (t + 1 < n_tiles) issue(t0 + kKT, BUF ^ 1);   // lands while this tile is consumed
+    block(buf_tag, K0{}, tail_tag, t0);
+    if (!TAIL || t0 + 32 < len) block(buf_tag, K1{}, tail_tag, t0);
+    dma_wait_all();
+    __syncthreads();  // next tile has landed for every wave; this tile is free to overwrite
+  };
+
   issue(0, 0);
   dma_wait_all();
   __syncthreads();
-
-  for (int t = 0; t < n_tiles; ++t) {
-    const int t0 = t * kKT;
-    const int buf = t & 1;
-    if (t + 1 < n_tiles) issue(t0 + kKT, buf ^ 1);   // lands while this tile is consumed
-    const bool tail = (t0 + kKT > len);
-    const __bf16* Kt = Ks[buf];
-    const __bf16* Vt = Vs[buf];
-
-#pragma unroll
-    for (int kb = 0; kb < kKT / 32; ++kb) {
-      if (t0 + kb * 32 >= len) break;  // whole block past the end (wave-uniform)
-      // ---- S^T block: 32 keys x 32 queries ----
-      floatx16 s;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-      for (int kk = 0; kk < KK; ++kk) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Kt[kb * 32 * D + k_off[kk]]);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], s, 0, 0, 0);
-      }
-      if (tail) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = t0 + kb * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-          if (key >= len) s[r] = -INFINITY;
-        }
-      }
-      // ---- online softmax (per lane: one query, 16 keys; partner lane^32 has the other 16) ----
-      float mx = s[0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-      mx = pair_max(mx);
-      const float m_new = fmaxf(m_run, mx);   // finite: the block holds a valid key
-      const float mc = m_new * c2;
-      float psum = 0.f;
-      bf16x8 pf[2];
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(s[r], c2, -mc));
-        psum += p;
-        pf[r >> 3][r & 7] = (__bf16)p;
-      }
-      if (__any(m_new > m_run)) {
-        const float a = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-        l_run *= a;
-#pragma unroll
-        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) o[mb][r] *= a;
-      }
-      l_run += psum;
-      m_run = m_new;
-      // ---- O^T += V^T P^T ----
-#pragma unroll
-      for (int mb = 0; mb < MB; ++mb) {
-#pragma unroll
-        for (int sg = 0; sg < 2; ++sg) {
-          const __bf16* vp = &Vt[(kb * 32 + 16 * sg) * D + v_off[mb]];
-          const bf16x4 v0 = lds_read_tr(vp);
-          const bf16x4 v1 = lds_read_tr(vp + 8 * D);
-          bf16x8 vf;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            vf[i] = v0[i];
-            vf[4 + i] = v1[i];
-          }
-          o[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[sg], o[mb], 0, 0, 0);
-        }
-      }
-    }
-    dma_wait_all();
-    __syncthreads();  // next tile has landed for every wave; this tile is free to overwrite
+  int t = 0;
+  for (; t + 2 <= n_full; t += 2) {
+    tile(B0{}, std::false_type{}, t);
+    tile(B1{}, std::false_type{}, t + 1);
+  }
+  if (t < n_full) {
+    tile(B0{}, std::false_type{}, t);
+    if (n_tiles > n_full) tile(B1{}, std::true_type{}, t + 1);
+  } else if (n_tiles > n_full) {
+    tile(B0{}, std::true_type{}, t);
   }
 
   // ---- normalise and store: lane holds query col, head-dim rows 32mb + 8(r/4) + 4h + r%4 ----
