@@ -77,25 +77,39 @@ __device__ __forceinline__ double shfl_xor_f64(double v, int m) {
   return __hiloint2double(hi, lo);
 }
 
-// Combine the per-chunk (max, sum) partials of one unit: rows i < n_obs handled
-// by threads i < 32; result in sm[i] (max) and sinv[i] (1 / normaliser).
+// Combine the per-chunk (reference, sum) partials of one unit into sm[i]
+// (reference) and sinv[i] (1 / normaliser) for the rows i < n_obs.  All 256
+// threads take part: thread (g, i) = (tid / 32, tid % 32) folds the chunks
+// g, g + 8, ... of row i, then the eight groups are merged through LDS.
 // LOG2: the partials are in log2 units (MFMA path) instead of natural units.
+// Ends with a barrier: sm / sinv are ready for every thread on return.
 template <bool LOG2>
 __device__ __forceinline__ void combine_stats(const double* __restrict__ st, int n_chunks, int n_obs,
-                                              double* sm, double* sinv) {
-  const int i = threadIdx.x;
-  if (i < kMaxObs) {
-    double m = -INFINITY, l = 0.0;
-    if (i < n_obs) {
-      for (int c = 0; c < n_chunks; ++c) m = fmax(m, st[(c * kMaxObs + i) * 2]);
-      for (int c = 0; c < n_chunks; ++c) {
-        const double mc = st[(c * kMaxObs + i) * 2], lc = st[(c * kMaxObs + i) * 2 + 1];
-        l += lc * (LOG2 ? (double)exp2_split(mc - m) : exp_neg(mc - m));
-      }
-    }
+                                              double* sm, double* sinv, double (*red)[kMaxObs]) {
+  const int i = threadIdx.x & 31, g = threadIdx.x >> 5;
+  double m = -INFINITY;
+  for (int c = g; c < n_chunks; c += 8) m = fmax(m, st[(c * kMaxObs + i) * 2]);
+  red[g][i] = m;
+  __syncthreads();
+  m = red[0][i];
+#pragma unroll
+  for (int k = 1; k < 8; ++k) m = fmax(m, red[k][i]);
+  __syncthreads();
+  double l = 0.0;
+  for (int c = g; c < n_chunks; c += 8) {
+    const double mc = st[(c * kMaxObs + i) * 2], lc = st[(c * kMaxObs + i) * 2 + 1];
+    l += lc * (LOG2 ? (double)exp2_split(mc - m) : exp_neg(mc - m));
+  }
+  red[g][i] = l;
+  __syncthreads();
+  if (g == 0) {
+    l = red[0][i];
+#pragma unroll
+    for (int k = 1; k < 8; ++k) l += red[k][i];
     sm[i] = (i < n_obs) ? m : 0.0;  // unused rows: finite shift, zero weight
     sinv[i] = (i < n_obs) ? 1.0 / l : 0.0;
   }
+  __syncthreads();
 }
 
 // ---------------------------------------------------------------------------
@@ -115,7 +129,7 @@ __global__ __launch_bounds__(kThreads) void score_generic(
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
 
   __shared__ float qs[kMaxObs][D];
-  __shared__ double red[4][kMaxObs];
+  __shared__ double red[8][kMaxObs];
   __shared__ double sm[kMaxObs], sinv[kMaxObs];
 
   for (int e = tid; e < n_obs * D; e += kThreads) {
@@ -123,7 +137,7 @@ __global__ __launch_bounds__(kThreads) void score_generic(
     qs[i][c] = to_float(q[((int64_t)d.unit * N_k + q_rows[i]) * D + c]);
   }
   double* st_unit = stats + (int64_t)blockIdx.y * max_chunks * kMaxObs * 2;
-  if (PASS == 2) combine_stats<false>(st_unit, n_chunks, n_obs, sm, sinv);
+  if (PASS == 2) combine_stats<false>(st_unit, n_chunks, n_obs, sm, sinv, red);
   __syncthreads();
 
   const int j = key0 + tid;
@@ -199,6 +213,7 @@ __global__ __launch_bounds__(kThreads) void score_mfma(
 
   __shared__ double sm[kMaxObs], sinv[kMaxObs];
   __shared__ float redm[4][kMaxObs], redl[4][kMaxObs];
+  __shared__ double redc[8][kMaxObs];
   double* st_unit = stats + (int64_t)blockIdx.y * max_chunks * kMaxObs * 2;
 
   // K fragments of this wave's tiles: issue every load before anything else.
@@ -227,7 +242,7 @@ __global__ __launch_bounds__(kThreads) void score_mfma(
       qf[kk] = qv ? *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * half) : z;
     }
   }
-  if (PASS == 2) combine_stats<true>(st_unit, n_chunks, n_obs, sm, sinv);
+  if (PASS == 2) combine_stats<true>(st_unit, n_chunks, n_obs, sm, sinv, redc);
 
   // Raw dot products: every MFMA covers 16 head-dim elements and starts from a
   // zero accumulator; the slice results are summed in fp64, so float32 rounding
