@@ -38,7 +38,9 @@ struct hack_ctx {
   // workspace
   float* importance = nullptr;   // [max_units, ws_stride]
   int32_t* kept = nullptr;       // [max_units, ws_stride]
-  double* stats = nullptr;       // [max_units, max_chunks, 32, 2]
+  double* stats = nullptr;       // [max_units, max_chunks, 32, 2] softmax partials
+  double* rowstat = nullptr;     // [max_units, 32] per-row softmax sums, zero between launches
+  unsigned* counters = nullptr;  // [max_units] chunk arrival counters, zero between launches
   int64_t ws_stride = 0;
   int max_chunks = 0;
   // launch-table cache
@@ -216,6 +218,21 @@ void build_attn_items(const std::vector<UnitDesc>& descs, int N_k, int tile_rows
     for (size_t i = 0; i < per[x].size(); ++i) (*items)[i * X + x] = per[x][i];
 }
 
+// One score work item per chunk of every listed unit, longest units first so the
+// tail of the launch is made of short units.
+void build_score_items(const std::vector<UnitDesc>& descs, const std::vector<int32_t>& list, int item_keys,
+                       std::vector<ScoreItemHost>* items) {
+  items->clear();
+  std::vector<int> order(list.size());
+  for (size_t i = 0; i < list.size(); ++i) order[i] = (int)i;
+  auto t_in = [&](int pos) { return descs[list[pos]].len_in + descs[list[pos]].n_new; };
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return t_in(a) > t_in(b); });
+  for (int pos : order) {
+    const int chunks = (t_in(pos) + item_keys - 1) / item_keys;
+    for (int c = 0; c < chunks; ++c) items->push_back(ScoreItemHost{pos, c});
+  }
+}
+
 void fill_q_rows(const int32_t* q_idx, int n_obs, int N_k, int32_t* rows) {
   for (int i = 0; i < kMaxObs; ++i) rows[i] = 0;
   for (int i = 0; i < n_obs; ++i) rows[i] = q_idx ? q_idx[i] : (int32_t)(((int64_t)i * N_k) / n_obs);
@@ -252,12 +269,17 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   ctx->cfg = *cfg;
   ctx->elem_bytes = cfg->dtype == HACK_F32 ? 4 : 2;
   ctx->ws_stride = round_up(cfg->max_cache_len, 64);
-  ctx->max_chunks = (cfg->max_cache_len + kScoreChunk - 1) / kScoreChunk;
+  ctx->max_chunks = (cfg->max_cache_len + kScoreMinChunk - 1) / kScoreMinChunk;
   hipError_t e = hipSetDevice(cfg->device);
   const size_t n_ws = (size_t)cfg->max_units * ctx->ws_stride;
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->importance, n_ws * sizeof(float));
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->kept, n_ws * sizeof(int32_t));
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->stats, (size_t)cfg->max_units * ctx->max_chunks * kMaxObs * 2 * sizeof(double));
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->rowstat, (size_t)cfg->max_units * kMaxObs * 2 * sizeof(double));
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, (size_t)cfg->max_units * sizeof(unsigned));
+  if (e == hipSuccess) e = hipMemset(ctx->counters, 0, (size_t)cfg->max_units * sizeof(unsigned));
+  if (e == hipSuccess) e = hipMemset(ctx->rowstat, 0, (size_t)cfg->max_units * kMaxObs * 2 * sizeof(double));
+  if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->arena_dev, kArenaBytes);
   if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->arena_host, kArenaBytes, hipHostMallocDefault);
   if (e != hipSuccess) {
@@ -273,6 +295,8 @@ extern "C" void hack_destroy(hack_ctx* ctx) {
   if (ctx->importance) (void)hipFree(ctx->importance);
   if (ctx->kept) (void)hipFree(ctx->kept);
   if (ctx->stats) (void)hipFree(ctx->stats);
+  if (ctx->rowstat) (void)hipFree(ctx->rowstat);
+  if (ctx->counters) (void)hipFree(ctx->counters);
   if (ctx->arena_dev) (void)hipFree(ctx->arena_dev);
   if (ctx->arena_host) (void)hipHostFree(ctx->arena_host);
   delete ctx;
@@ -316,16 +340,19 @@ extern "C" hack_status hack_score(hack_ctx* ctx, int32_t B, int32_t N_k, const v
   if (descs.empty()) return HACK_OK;
   int32_t rows[kMaxObs];
   fill_q_rows(q_idx, n_obs, N_k, rows);
+  std::vector<ScoreItemHost> sitems;
+  build_score_items(descs, list, score_item_keys(ctx->cfg.dtype), &sitems);
   Table t;
   const size_t o_desc = t.add(descs.data(), descs.size());
   const size_t o_list = t.add(list.data(), list.size());
   const size_t o_rows = t.add(rows, kMaxObs);
+  const size_t o_sit = t.add(sitems.data(), sitems.size());
   const uint8_t* dev;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
   launch_score(s, ctx->cfg.dtype, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), (const int32_t*)(dev + o_list),
-               (int)list.size(), max_t, q, (const int32_t*)(dev + o_rows), n_obs, N_k, scale, in->k, k_new,
-               ctx->stats, importance, imp_stride);
+               (int)list.size(), max_t, dev + o_sit, (int)sitems.size(), q, (const int32_t*)(dev + o_rows), n_obs,
+               N_k, scale, in->k, k_new, ctx->stats, ctx->rowstat, ctx->counters, importance, imp_stride);
   HIP_TRY(ctx, hipGetLastError());
   return HACK_OK;
 }
@@ -572,11 +599,14 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
   std::vector<AttnItem> items;
   build_attn_items(descs, N_k, tile, &items);
 
+  std::vector<ScoreItemHost> sitems;
+  build_score_items(descs, comp, score_item_keys(ctx->cfg.dtype), &sitems);
   Table t;
   const size_t o_desc = t.add(descs.data(), descs.size());
   const size_t o_comp = t.add(comp.data(), comp.size());
   const size_t o_rows = t.add(rows, kMaxObs);
   const size_t o_items = t.add(items.data(), items.size());
+  const size_t o_sit = t.add(sitems.data(), sitems.size());
   const uint8_t* dev;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
@@ -584,9 +614,9 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
   CachePtrs cp{cache->k, cache->v, cache->pos};
 
   if (!comp.empty()) {
-    launch_score(s, ctx->cfg.dtype, ctx->cfg.head_dim, ddev, (const int32_t*)(dev + o_comp), (int)comp.size(), max_t, q,
-                 (const int32_t*)(dev + o_rows), n_obs, N_k, scale, cache->k, k_new, ctx->stats, ctx->importance,
-                 ctx->ws_stride);
+    launch_score(s, ctx->cfg.dtype, ctx->cfg.head_dim, ddev, (const int32_t*)(dev + o_comp), (int)comp.size(), max_t,
+                 dev + o_sit, (int)sitems.size(), q, (const int32_t*)(dev + o_rows), n_obs, N_k, scale, cache->k, k_new,
+                 ctx->stats, ctx->rowstat, ctx->counters, ctx->importance, ctx->ws_stride);
     launch_select(s, ddev, (const int32_t*)(dev + o_comp), (int)comp.size(), max_t, ctx->importance, ctx->ws_stride, kept,
                   kstride);
   }

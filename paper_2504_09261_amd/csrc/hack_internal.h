@@ -41,7 +41,8 @@ struct CachePtrs {
   int32_t* pos;
 };
 
-constexpr int kScoreChunk = 256;   // keys per score work-group
+constexpr int kScoreChunk = 256;   // keys per score work-group (fp32 path)
+constexpr int kScoreMinChunk = 128; // smallest chunk any score path uses (sizes the partials workspace)
 constexpr int kMaxObs = 32;        // observation queries (one MFMA column block)
 
 // ---- kernel launchers (each validates nothing: the API layer has done so) ----
@@ -53,12 +54,21 @@ void launch_move(hipStream_t s, int elem_bytes, int head_dim, const UnitDesc* de
                  int max_rows, CachePtrs in, CachePtrs out, const void* k_new, const void* v_new,
                  int N_k, int pos_new, const int32_t* kept_idx, int64_t idx_stride);
 
-// Subset-attention importance.  list[n_list] indexes descs; stats is a
-// workspace of n_list * max_chunks * 64 doubles; q_rows DEVICE int32[n_obs].
+// Subset-attention importance.  list[n_list] indexes descs; items (bf16 only) is
+// a DEVICE array of n_items {position in list, chunk} pairs, one per chunk of
+// score_item_keys() keys of every listed unit; stats is a workspace of
+// n_list * ceil(max_t_in / score_item_keys) * 64 doubles, rowstat of n_list * 64
+// doubles, counters of n_list zeroed uint32 (left zeroed); q_rows DEVICE int32[32].
+struct ScoreItemHost {
+  int32_t pos;
+  int32_t chunk;
+};
+int score_item_keys(int dtype);
 void launch_score(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, const int32_t* list,
-                  int n_list, int max_t_in, const void* q, const int32_t* q_rows, int n_obs, int N_k,
-                  float scale, const void* k_cache, const void* k_new, double* stats,
-                  float* importance, int64_t imp_stride);
+                  int n_list, int max_t_in, const void* items, int n_items, const void* q,
+                  const int32_t* q_rows, int n_obs, int N_k, float scale, const void* k_cache,
+                  const void* k_new, double* stats, double* rowstat, unsigned* counters, float* importance,
+                  int64_t imp_stride);
 
 // Budgeted selection; one work-group per listed unit.
 void launch_select(hipStream_t s, const UnitDesc* descs, const int32_t* list, int n_list,
