@@ -22,6 +22,7 @@ sys.path.insert(0, ROOT)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16
 HBM_PEAK_GBPS = 8000.0             # MI355X HBM3E
+COPY_CALIBRATION_BYTES = 1 << 30   # read and written per launch in --mode copy
 FP32_VALU_PEAK_TFLOPS = 157.3
 
 
@@ -32,7 +33,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--config", type=int, default=2, help="workload family 0..4 (default: Infinity-2B-shaped 1024^2)")
     ap.add_argument("--layers", type=int, default=2, help="distinct layers of inputs kept resident and cycled")
-    ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
+    ap.add_argument("--mode", choices=["graph", "eager", "copy"], default="graph",
+                    help="graph/eager: how the schedule is launched; copy: only run a plain 1 GiB-in/1 GiB-out "
+                         "elementwise kernel --steps times (the known-size reference for HBM counter calibration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
     ap.add_argument("--batch", type=int, default=None)
@@ -174,6 +177,20 @@ def cpu_baseline(cfg, layer, wl, budget_s=15.0):
                        f"{spent:.1f} s measured, scaled by class counts ({n_c} contextual, {n_s} structural)")
 
 
+def committed_traffic(cfg, kernel):
+    """HBM bytes per launch of `kernel` on this workload from the committed
+    counter summary (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, calibrated on
+    a plain copy); None when no summary for this workload is present."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{kernel}_cfg{cfg.cfg_id}_hbm_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch"):
+                return float(line.split("=")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -184,8 +201,18 @@ def main():
     from paper_2504_09261_amd import workload as wl
     from paper_2504_09261_amd.binding import Hack
 
-    cfg = wl.get_config(args.config, batch=args.batch)
     torch.cuda.set_device(0)
+    if args.mode == "copy":
+        n = COPY_CALIBRATION_BYTES // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(args.steps):
+            torch.mul(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "copy", "launches": args.steps, "bytes_read_per_launch": 4 * n,
+                          "bytes_written_per_launch": 4 * n}))
+        return
+    cfg = wl.get_config(args.config, batch=args.batch)
     hk = Hack(cfg.heads, cfg.head_dim, cfg.dtype, cfg.n_units, cfg.T_K, max(cfg.N), cfg.n_obs)
     layers = [LayerState(hk, cfg, l, wl, torch) for l in range(args.layers)]
 
@@ -246,7 +273,7 @@ def main():
         tf_big = sum(work[i]["attn_flop"] for i in big) / (sum(bd["attn"][i] for i in big) * 1e-3) / 1e12
         result["roofline"] = {
             "bound": "mfma", "kernel": "attn_mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
-            "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+            "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": committed_traffic(cfg, "attn_mfma"),
             "launches_per_layer": n_attn, "avg_launch_us": attn_ms * 1e3 / n_attn,
             "flop_per_launch": tot["attn_flop"] / n_attn,
             "large_steps": {"steps": [i + 1 for i in big], "achieved": tf_big,
