@@ -24,6 +24,9 @@ namespace {
 
 constexpr size_t kArenaBytes = 32u << 20;  // launch tables (device + pinned mirror)
 constexpr size_t kAlign = 256;
+// Polls (each an atomic round trip plus a short sleep, ~1 us) a score wave spends waiting for the
+// other items of its unit before it gives up; real waits last a few microseconds.
+constexpr int kScoreSpinLimit = 1 << 18;
 
 struct TableEntry {
   size_t offset;  // into both arenas
@@ -38,9 +41,11 @@ struct hack_ctx {
   // workspace
   float* importance = nullptr;   // [max_units, ws_stride]
   int32_t* kept = nullptr;       // [max_units, ws_stride]
-  double* stats = nullptr;       // [max_units, max_chunks, 32, 2] softmax partials
-  double* rowstat = nullptr;     // [max_units, 32] per-row softmax sums, zero between launches
-  unsigned* counters = nullptr;  // [max_units] chunk arrival counters, zero between launches
+  double* stats = nullptr;       // fp32 path: [max_units, max_chunks, 32, 2] softmax partials
+  double* rowstat = nullptr;     // bf16 path: [max_units, 32] softmax normalisers, zero between launches
+  unsigned* counters = nullptr;  // bf16 path: [max_units, 2] arrival / reader counters, zero between launches
+  int* fault = nullptr;          // pinned, device-visible: set by a score wave whose bounded wait gave up
+  int score_capacity = 0;        // bf16 path: score items one launch may hold (resident waves)
   int64_t ws_stride = 0;
   int max_chunks = 0;
   // launch-table cache
@@ -168,6 +173,9 @@ void plan_select(int type, int T, int b, int n_init, int n_recent, UnitDesc* d) 
 
 hack_status check_common(hack_ctx* ctx, int32_t B, int32_t N_k, bool need_nk) {
   if (!ctx) return HACK_EINVAL;
+  if (ctx->fault && *(volatile int*)ctx->fault)
+    return fail(ctx, HACK_EHIP, "an earlier score launch gave up waiting for a unit's work items; its importance "
+                                "output is incomplete and this context is no longer usable");
   if (B < 1) return fail(ctx, HACK_EINVAL, "B must be >= 1 (got %d)", B);
   if ((int64_t)B * ctx->cfg.heads > ctx->cfg.max_units)
     return fail(ctx, HACK_ECAPACITY, "B*H = %lld exceeds max_units %d", (long long)B * ctx->cfg.heads, ctx->cfg.max_units);
@@ -219,18 +227,41 @@ void build_attn_items(const std::vector<UnitDesc>& descs, int N_k, int tile_rows
 }
 
 // One score work item per chunk of every listed unit, longest units first so the
-// tail of the launch is made of short units.
+// tail of a launch is made of short units.  All items of a unit go into the same
+// launch group and no group exceeds `capacity` items; group_begin gets the first
+// item of every group plus the total as its last entry.
 void build_score_items(const std::vector<UnitDesc>& descs, const std::vector<int32_t>& list, int item_keys,
-                       std::vector<ScoreItemHost>* items) {
+                       int capacity, std::vector<ScoreItem>* items, std::vector<int>* group_begin) {
   items->clear();
+  group_begin->assign(1, 0);
   std::vector<int> order(list.size());
   for (size_t i = 0; i < list.size(); ++i) order[i] = (int)i;
   auto t_in = [&](int pos) { return descs[list[pos]].len_in + descs[list[pos]].n_new; };
   std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return t_in(a) > t_in(b); });
   for (int pos : order) {
-    const int chunks = (t_in(pos) + item_keys - 1) / item_keys;
-    for (int c = 0; c < chunks; ++c) items->push_back(ScoreItemHost{pos, c});
+    const UnitDesc& d = descs[list[pos]];
+    const int wgs = ((t_in(pos) + item_keys - 1) / item_keys + 3) / 4;  // 4 items per work-group, same unit
+    if ((int)items->size() - group_begin->back() + 4 * wgs > capacity) group_begin->push_back((int)items->size());
+    for (int c = 0; c < 4 * wgs; ++c)
+      items->push_back(ScoreItem{d.in_off, d.unit, d.len_in, t_in(pos), c, pos, wgs});
   }
+  group_begin->push_back((int)items->size());
+}
+
+// Scores the listed units of a table that is already on the device.
+void run_score(hack_ctx* ctx, hipStream_t s, const UnitDesc* ddev, const int32_t* list_dev, int n_list, int max_t,
+               const ScoreItem* items_dev, const std::vector<int>& group_begin, const void* q,
+               const int32_t* rows_dev, int n_obs, int N_k, float scale, const void* k_cache, const void* k_new,
+               float* importance, int64_t imp_stride) {
+  if (ctx->cfg.dtype == HACK_F32) {
+    launch_score_generic(s, ctx->cfg.head_dim, ddev, list_dev, n_list, max_t, q, rows_dev, n_obs, N_k, scale, k_cache,
+                         k_new, ctx->stats, importance, imp_stride);
+    return;
+  }
+  for (size_t g = 0; g + 1 < group_begin.size(); ++g)
+    launch_score_fused(s, ctx->cfg.head_dim, items_dev + group_begin[g], group_begin[g + 1] - group_begin[g], q,
+                       rows_dev, n_obs, N_k, scale, k_cache, k_new, ctx->rowstat, ctx->counters, importance,
+                       imp_stride, ctx->fault, kScoreSpinLimit);
 }
 
 void fill_q_rows(const int32_t* q_idx, int n_obs, int N_k, int32_t* rows) {
@@ -269,19 +300,28 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   ctx->cfg = *cfg;
   ctx->elem_bytes = cfg->dtype == HACK_F32 ? 4 : 2;
   ctx->ws_stride = round_up(cfg->max_cache_len, 64);
-  ctx->max_chunks = (cfg->max_cache_len + kScoreMinChunk - 1) / kScoreMinChunk;
+  ctx->max_chunks = (cfg->max_cache_len + kScoreChunk - 1) / kScoreChunk;
   hipError_t e = hipSetDevice(cfg->device);
   const size_t n_ws = (size_t)cfg->max_units * ctx->ws_stride;
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->importance, n_ws * sizeof(float));
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->kept, n_ws * sizeof(int32_t));
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->stats, (size_t)cfg->max_units * ctx->max_chunks * kMaxObs * 2 * sizeof(double));
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->rowstat, (size_t)cfg->max_units * kMaxObs * 2 * sizeof(double));
-  if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, (size_t)cfg->max_units * sizeof(unsigned));
-  if (e == hipSuccess) e = hipMemset(ctx->counters, 0, (size_t)cfg->max_units * sizeof(unsigned));
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, (size_t)cfg->max_units * 2 * sizeof(unsigned));
+  if (e == hipSuccess) e = hipMemset(ctx->counters, 0, (size_t)cfg->max_units * 2 * sizeof(unsigned));
+  if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->fault, sizeof(int), hipHostMallocDefault);
+  if (e == hipSuccess) *ctx->fault = 0;
   if (e == hipSuccess) e = hipMemset(ctx->rowstat, 0, (size_t)cfg->max_units * kMaxObs * 2 * sizeof(double));
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->arena_dev, kArenaBytes);
   if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->arena_host, kArenaBytes, hipHostMallocDefault);
+  if (e == hipSuccess && cfg->dtype == HACK_BF16) {
+    // a unit's score items wait for each other inside one launch, so a launch may
+    // hold at most as many items as the device keeps resident at once
+    ctx->score_capacity = score_fused_capacity(cfg->head_dim);
+    const int per_unit = (cfg->max_cache_len + score_item_keys(cfg->dtype) - 1) / score_item_keys(cfg->dtype) + 3;
+    if (ctx->score_capacity < per_unit) e = hipErrorInvalidConfiguration;
+  }
   if (e != hipSuccess) {
     hack_destroy(ctx);
     return HACK_EHIP;
@@ -297,6 +337,7 @@ extern "C" void hack_destroy(hack_ctx* ctx) {
   if (ctx->stats) (void)hipFree(ctx->stats);
   if (ctx->rowstat) (void)hipFree(ctx->rowstat);
   if (ctx->counters) (void)hipFree(ctx->counters);
+  if (ctx->fault) (void)hipHostFree(ctx->fault);
   if (ctx->arena_dev) (void)hipFree(ctx->arena_dev);
   if (ctx->arena_host) (void)hipHostFree(ctx->arena_host);
   delete ctx;
@@ -340,8 +381,10 @@ extern "C" hack_status hack_score(hack_ctx* ctx, int32_t B, int32_t N_k, const v
   if (descs.empty()) return HACK_OK;
   int32_t rows[kMaxObs];
   fill_q_rows(q_idx, n_obs, N_k, rows);
-  std::vector<ScoreItemHost> sitems;
-  build_score_items(descs, list, score_item_keys(ctx->cfg.dtype), &sitems);
+  std::vector<ScoreItem> sitems;
+  std::vector<int> groups;
+  if (ctx->cfg.dtype == HACK_BF16)
+    build_score_items(descs, list, score_item_keys(ctx->cfg.dtype), ctx->score_capacity, &sitems, &groups);
   Table t;
   const size_t o_desc = t.add(descs.data(), descs.size());
   const size_t o_list = t.add(list.data(), list.size());
@@ -350,9 +393,9 @@ extern "C" hack_status hack_score(hack_ctx* ctx, int32_t B, int32_t N_k, const v
   const uint8_t* dev;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
-  launch_score(s, ctx->cfg.dtype, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), (const int32_t*)(dev + o_list),
-               (int)list.size(), max_t, dev + o_sit, (int)sitems.size(), q, (const int32_t*)(dev + o_rows), n_obs,
-               N_k, scale, in->k, k_new, ctx->stats, ctx->rowstat, ctx->counters, importance, imp_stride);
+  run_score(ctx, s, (const UnitDesc*)(dev + o_desc), (const int32_t*)(dev + o_list), (int)list.size(), max_t,
+            (const ScoreItem*)(dev + o_sit), groups, q, (const int32_t*)(dev + o_rows), n_obs, N_k, scale, in->k, k_new,
+            importance, imp_stride);
   HIP_TRY(ctx, hipGetLastError());
   return HACK_OK;
 }
@@ -599,8 +642,10 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
   std::vector<AttnItem> items;
   build_attn_items(descs, N_k, tile, &items);
 
-  std::vector<ScoreItemHost> sitems;
-  build_score_items(descs, comp, score_item_keys(ctx->cfg.dtype), &sitems);
+  std::vector<ScoreItem> sitems;
+  std::vector<int> groups;
+  if (ctx->cfg.dtype == HACK_BF16)
+    build_score_items(descs, comp, score_item_keys(ctx->cfg.dtype), ctx->score_capacity, &sitems, &groups);
   Table t;
   const size_t o_desc = t.add(descs.data(), descs.size());
   const size_t o_comp = t.add(comp.data(), comp.size());
@@ -614,9 +659,9 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
   CachePtrs cp{cache->k, cache->v, cache->pos};
 
   if (!comp.empty()) {
-    launch_score(s, ctx->cfg.dtype, ctx->cfg.head_dim, ddev, (const int32_t*)(dev + o_comp), (int)comp.size(), max_t,
-                 dev + o_sit, (int)sitems.size(), q, (const int32_t*)(dev + o_rows), n_obs, N_k, scale, cache->k, k_new,
-                 ctx->stats, ctx->rowstat, ctx->counters, ctx->importance, ctx->ws_stride);
+    run_score(ctx, s, ddev, (const int32_t*)(dev + o_comp), (int)comp.size(), max_t, (const ScoreItem*)(dev + o_sit),
+              groups, q, (const int32_t*)(dev + o_rows), n_obs, N_k, scale, cache->k, k_new, ctx->importance,
+              ctx->ws_stride);
     launch_select(s, ddev, (const int32_t*)(dev + o_comp), (int)comp.size(), max_t, ctx->importance, ctx->ws_stride, kept,
                   kstride);
   }

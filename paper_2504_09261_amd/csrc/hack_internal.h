@@ -42,7 +42,6 @@ struct CachePtrs {
 };
 
 constexpr int kScoreChunk = 256;   // keys per score work-group (fp32 path)
-constexpr int kScoreMinChunk = 128; // smallest chunk any score path uses (sizes the partials workspace)
 constexpr int kMaxObs = 32;        // observation queries (one MFMA column block)
 
 // ---- kernel launchers (each validates nothing: the API layer has done so) ----
@@ -54,21 +53,37 @@ void launch_move(hipStream_t s, int elem_bytes, int head_dim, const UnitDesc* de
                  int max_rows, CachePtrs in, CachePtrs out, const void* k_new, const void* v_new,
                  int N_k, int pos_new, const int32_t* kept_idx, int64_t idx_stride);
 
-// Subset-attention importance.  list[n_list] indexes descs; items (bf16 only) is
-// a DEVICE array of n_items {position in list, chunk} pairs, one per chunk of
-// score_item_keys() keys of every listed unit; stats is a workspace of
-// n_list * ceil(max_t_in / score_item_keys) * 64 doubles, rowstat of n_list * 64
-// doubles, counters of n_list zeroed uint32 (left zeroed); q_rows DEVICE int32[32].
-struct ScoreItemHost {
-  int32_t pos;
-  int32_t chunk;
+// Subset-attention importance, bf16: one launch over `items`, a DEVICE array with
+// one entry per chunk of score_item_keys() keys of every scored unit, each unit
+// padded with empty chunks to a multiple of 4 entries (one work-group takes 4
+// consecutive entries, which must belong to one unit).  All items of a unit
+// must be in the same launch and n_items must not exceed
+// score_fused_capacity() (the waves the device holds at once: the kernel waits
+// inside a launch for a unit's items).  rowsum is a workspace of 32 doubles and
+// counters of 2 uint32 per `pos`, all zero on entry and left zero; q_rows DEVICE
+// int32[32]; *fault (host-visible) is set if a wait gave up after spin_limit polls.
+struct alignas(16) ScoreItem {
+  int64_t in_off;    // first row of the unit's cached keys
+  int32_t unit;      // u = b*H + h (rows of q/k_new start at u*N_k)
+  int32_t len_in;    // cached keys
+  int32_t t_in;      // cached + new keys
+  int32_t chunk;     // this item covers keys [chunk*keys, (chunk+1)*keys)
+  int32_t pos;       // workspace slot of the unit
+  int32_t n_groups;  // work-groups (sets of 4 items) of the unit
 };
+static_assert(sizeof(ScoreItem) == 32, "ScoreItem must stay 32 bytes");
 int score_item_keys(int dtype);
-void launch_score(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, const int32_t* list,
-                  int n_list, int max_t_in, const void* items, int n_items, const void* q,
-                  const int32_t* q_rows, int n_obs, int N_k, float scale, const void* k_cache,
-                  const void* k_new, double* stats, double* rowstat, unsigned* counters, float* importance,
-                  int64_t imp_stride);
+int score_fused_capacity(int head_dim);
+void launch_score_fused(hipStream_t s, int head_dim, const ScoreItem* items, int n_items, const void* q,
+                        const int32_t* q_rows, int n_obs, int N_k, float scale, const void* k_cache,
+                        const void* k_new, double* rowsum, unsigned* counters, float* importance,
+                        int64_t imp_stride, int* fault, int spin_limit);
+// fp32: two passes over (chunk of 256 keys, listed unit); list[n_list] indexes
+// descs; stats is a workspace of n_list * ceil(max_t_in / 256) * 64 doubles.
+void launch_score_generic(hipStream_t s, int head_dim, const UnitDesc* descs, const int32_t* list, int n_list,
+                          int max_t_in, const void* q, const int32_t* q_rows, int n_obs, int N_k, float scale,
+                          const void* k_cache, const void* k_new, double* stats, float* importance,
+                          int64_t imp_stride);
 
 // Budgeted selection; one work-group per listed unit.
 void launch_select(hipStream_t s, const UnitDesc* descs, const int32_t* list, int n_list,

@@ -4,23 +4,24 @@
 // over the uncompressed keys of the step (cache rows followed by the current
 // scale's rows, read from their two homes without materialising the concat).
 //
-// The column sum needs each row's softmax normaliser before any key's
-// importance can be formed, so the work is split in two streaming passes over
-// K, both tiled as (unit, chunk of 256 keys):
+// The column sum needs each row's softmax normaliser l_i before any key's
+// importance can be formed.
+//
+// bf16 (score_fused): one launch that reads K once.  One
+// v_mfma_f32_32x32x16_bf16 column block holds all 32 observation rows; a wave
+// takes 128 keys as four 32-key tiles copied HBM -> LDS asynchronously, parks
+// the logits in registers, contributes to the unit's l_i through fp64 atomics,
+// waits (bounded) for the other work-groups of the unit and then writes
+// importance_j = sum_i 2^t_ij / l_i from the parked logits.
+// fp32 (score_generic): two streaming passes over (unit, chunk of 256 keys),
+// plain fp64 FMA dot products, one key per lane:
 //   pass 1  per chunk and observation row: max logit and sum of exp(logit - max)
 //   pass 2  combine the chunk partials of the unit, recompute the logits and
 //           write importance[j] = sum_i exp(s_ij - m_i) / l_i.
-// Both passes are bound by reading K (n_obs <= 32 rows against every key is a
-// skinny product, ~31 flop per byte), so the spare ALU is spent on accuracy:
-// the logit is widened to fp64 before the shift and the exponential is
-// range-reduced in fp64, which keeps float32 importance within a few ulp of the
-// exact value; the ranking that follows is decided on those float32 numbers.
-//
-// bf16: one v_mfma_f32_32x32x16_bf16 column block holds all 32 observation
-// rows; a wave owns 64 keys (two 32-key tiles), loads its K fragments straight
-// from HBM into registers (each key is used once per wave: staging in LDS would
-// buy nothing), and reduces over keys in-lane first, across lanes once.
-// fp32: plain fp64 FMA dot products, one key per lane.
+// n_obs <= 32 rows against every key is a skinny product (~31 flop per byte), so
+// ALU is spent on accuracy: logits are accumulated in fp64 and the exponential
+// is range-reduced exactly, which keeps float32 importance within a few ulp of
+// the exact value; the ranking that follows is decided on those float32 numbers.
 #include "hack_internal.h"
 
 namespace hack {
@@ -42,30 +43,6 @@ __device__ __forceinline__ float exp2_split(double t) {
   return ldexpf(__builtin_amdgcn_exp2f(r), (int)n);
 }
 __device__ __forceinline__ double exp_neg(double x) { return (double)exp2_split(x * kLog2e); }
-
-// All-reduce over the 32 lanes of a half-wave without touching LDS memory:
-// two quad permutes, the two row mirrors, then a swizzle across the 16-lane rows.
-template <int CTRL>
-__device__ __forceinline__ float dpp_mov(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
-}
-__device__ __forceinline__ float swz_xor16(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));
-}
-__device__ __forceinline__ float half_max(float v) {
-  v = fmaxf(v, dpp_mov<0xB1>(v));
-  v = fmaxf(v, dpp_mov<0x4E>(v));
-  v = fmaxf(v, dpp_mov<0x141>(v));
-  v = fmaxf(v, dpp_mov<0x140>(v));
-  return fmaxf(v, swz_xor16(v));
-}
-__device__ __forceinline__ float half_sum(float v) {
-  v += dpp_mov<0xB1>(v);
-  v += dpp_mov<0x4E>(v);
-  v += dpp_mov<0x141>(v);
-  v += dpp_mov<0x140>(v);
-  return v + swz_xor16(v);
-}
 
 __device__ __forceinline__ float to_float(float v) { return v; }
 __device__ __forceinline__ float to_float(__bf16 v) { return (float)v; }
@@ -200,9 +177,9 @@ __device__ __forceinline__ int c_row(int r, int half) { return 8 * (r >> 2) + 4 
 // wave copies its 32-key tiles HBM -> LDS with global_load_lds (16 B per lane,
 // whole rows, fully coalesced), double-buffered in a private LDS region, and
 // reads MFMA operands back with ds_read_b128 (XOR-swizzled chunks, conflict
-// free on the 64-bank LDS).  No work-group barrier anywhere: waves only wait on
-// their own copies (hand-placed s_waitcnt vmcnt), so they drift freely and keep
-// HBM busy.  Reading K fragments straight from HBM in operand layout would touch
+// free on the 64-bank LDS).  No work-group barrier while tiles stream: waves only
+// wait on their own copies (hand-placed s_waitcnt vmcnt), so they drift freely and
+// keep HBM busy.  Reading K fragments straight from HBM in operand layout would touch
 // 32 rows x 32 bytes per instruction and re-fetch every cache line several times.
 constexpr int kItemKeys = 128;                 // keys per wave item
 constexpr int kItemTiles = kItemKeys / 32;
@@ -226,20 +203,24 @@ template <int N> __device__ __forceinline__ void score_wait_vm() {
   __builtin_amdgcn_sched_barrier(0);
 }
 
-struct ScoreItem {
-  int32_t pos;     // position in the active-unit list (indexes the stats rows)
-  int32_t chunk;   // chunk index inside the unit
-};
-
-// 2^t as a double for any |t| <= 1000 (the float mantissa part is exact to ~1 ulp
-// of float32, the exponent is applied in fp64)
-__device__ __forceinline__ double exp2_wide(double t) {
-  t = fmin(fmax(t, -1000.0), 1000.0);
-  const double n = rint(t);
-  const float r = (float)(t - n);
-  return ldexp((double)__builtin_amdgcn_exp2f(r), (int)n);
+// Logits are parked in registers between the two halves of the fused kernel as
+// 32-bit fixed point, log2 units with 22 fractional bits: the quantisation moves
+// 2^t by at most ln2 * 2^-23 = 8.3e-8 relative, and both the normaliser and the
+// importance are formed from the same parked value.  |t| is clamped to 511
+// (354 nats), far outside anything a float32 importance can resolve.
+constexpr double kFixOne = 4194304.0;  // 2^22
+__device__ __forceinline__ int fix_from(double t_scaled) {  // t_scaled = t * 2^22
+  t_scaled = fmin(fmax(t_scaled, -511.0 * kFixOne), 511.0 * kFixOne);
+  return __double2int_rn(t_scaled);
 }
-// sum over the 32 lanes of a half-wave, fp64 (DPP moves of both dwords)
+__device__ __forceinline__ double exp2_fix(int qv) {
+  const int n = qv >> 22;
+  const float f = (float)(qv & 0x3FFFFF) * (float)(1.0 / kFixOne);  // [0, 1), exact
+  return ldexp((double)__builtin_amdgcn_exp2f(f), n);
+}
+// All-reduce sum over the 32 lanes of a half-wave, fp64, without touching LDS
+// memory: two quad permutes, the two row mirrors (DPP moves of both dwords),
+// then a swizzle across the 16-lane rows.
 template <int CTRL>
 __device__ __forceinline__ double dpp_mov_f64(double v) {
   const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, true);
@@ -256,23 +237,28 @@ __device__ __forceinline__ double half_sum_f64(double v) {
   return v + __hiloint2double(hi, lo);
 }
 
-// PASS 1: per item the sum over its keys of 2^t for every observation row
-//         (t = logit in log2 units; no running max is needed because the sums
-//         are kept in fp64, whose exponent range covers |t| <= 1000), added to
-//         the unit's 32 row sums with device-scope fp64 atomics.
-// PASS 2: every wave turns the row sums into (m_i, w_i), m_i an integer near
-//         log2(sum_i) and w_i = 2^m_i / sum_i, and writes
-//         importance_j = sum_i 2^(t_ij - m_i) * w_i.  The wave that finishes a
-//         unit's last chunk (atomic counter, nobody waits) zeroes the row sums
-//         and the counter again, so the workspace is clean for the next launch.
-template <int D, int PASS>
-__global__ __launch_bounds__(kThreads) void score_mfma(
-    const UnitDesc* __restrict__ descs, const int32_t* __restrict__ list,
-    const ScoreItem* __restrict__ items, int n_items, int max_chunks,
-    const __bf16* __restrict__ q, const int32_t* __restrict__ q_rows, int n_obs, int N_k,
-    float scale, const __bf16* __restrict__ k_cache, const __bf16* __restrict__ k_new,
-    double* __restrict__ rowsum, unsigned* __restrict__ counters,
-    float* __restrict__ importance, int64_t imp_stride) {
+// One launch, K read once.  Every wave
+//   A. forms the logits t_ij (log2 units) of its item, 32 observation rows x up
+//      to kItemKeys keys, and parks them in registers as fixed point;
+//   B. adds the row sums of p_ij = 2^t_ij (doubles: the fp64 exponent range makes
+//      a running maximum unnecessary) to the unit's 32 softmax normalisers l_i
+//      with device-scope fp64 atomics and bumps the unit's arrival counter;
+//   C. waits until all items of the unit have arrived, reads the l_i back and
+//      writes importance_j = sum_i p_ij / l_i for its keys.
+// The wait in C needs every item of a unit to be resident at the same time: the
+// host never launches more waves than the device holds at once (occupancy x
+// compute units), so all of them run concurrently and each arrives without
+// depending on anyone else.  The wait is bounded all the same: a wave that runs
+// out of polls raises *fault (host-visible) and leaves without writing, and the
+// host refuses further work on the context.  The wave that is last to read a
+// unit's sums zeroes sums and counters again for the next launch.
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void score_fused(
+    const ScoreItem* __restrict__ items, int n_items, const __bf16* __restrict__ q,
+    const int32_t* __restrict__ q_rows, int n_obs, int N_k, float scale,
+    const __bf16* __restrict__ k_cache, const __bf16* __restrict__ k_new,
+    double* __restrict__ rowsum, unsigned* __restrict__ counters, float* __restrict__ importance,
+    int64_t imp_stride, int* __restrict__ fault, int spin_limit) {
   constexpr int KK = D / 16;            // MFMA steps over the head dimension
   constexpr int CPR = D / 8;            // 16-byte chunks per row
   constexpr int RPI = 64 / CPR;         // rows per wave-wide copy instruction
@@ -281,19 +267,17 @@ __global__ __launch_bounds__(kThreads) void score_mfma(
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int item = blockIdx.x * 4 + w;
-  if (item >= n_items) return;          // wave-uniform; the kernel has no barriers
+  const int item = blockIdx.x * 4 + w;  // the host pads every unit to whole work-groups
   const ScoreItem it = items[item];
-  const UnitDesc d = descs[list[it.pos]];
-  const int T_in = d.len_in + d.n_new;
+  const int T_in = it.t_in;
   const int key0 = it.chunk * kItemKeys;
-  const int n_tiles = min(kItemTiles, (T_in - key0 + 31) / 32);
-  const int n_chunks = (T_in + kItemKeys - 1) / kItemKeys;
+  const int n_tiles = max(0, min(kItemTiles, (T_in - key0 + 31) / 32));  // 0: padding item
   const int col = lane & 31, half = lane >> 5;
 
   __shared__ __attribute__((aligned(1024))) __bf16 tiles[4][2][TILE];
   const unsigned lds0 = (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)&tiles[w][0][0];
   double* sum_unit = rowsum + (int64_t)it.pos * kMaxObs;
+  unsigned* cnt = counters + 2 * it.pos;   // [0] arrivals, [1] readers done
 
   // copy of tile t (keys key0 + 32t ..) into buffer t & 1.  A tile that lies
   // wholly inside the cached rows or wholly inside the new rows (the common
@@ -309,11 +293,11 @@ __global__ __launch_bounds__(kThreads) void score_mfma(
   auto issue = [&](int t) {
     const int j0 = key0 + t * 32;
     const unsigned dst = lds0 + (unsigned)((t & 1) * TILE * 2);
-    const bool in_cache = j0 + 32 <= d.len_in;
-    const bool in_new = j0 >= d.len_in && j0 + 32 <= T_in;
+    const bool in_cache = j0 + 32 <= it.len_in;
+    const bool in_new = j0 >= it.len_in && j0 + 32 <= T_in;
     if (in_cache || in_new) {
-      const __bf16* base = in_cache ? k_cache + (d.in_off + j0) * D
-                                    : k_new + ((int64_t)d.unit * N_k + (j0 - d.len_in)) * D;
+      const __bf16* base = in_cache ? k_cache + (it.in_off + j0) * D
+                                    : k_new + ((int64_t)it.unit * N_k + (j0 - it.len_in)) * D;
 #pragma unroll
       for (int i = 0; i < IPT; ++i) score_dma16_base(base, src_off[i], dst + i * 1024);
     } else {
@@ -321,112 +305,147 @@ __global__ __launch_bounds__(kThreads) void score_mfma(
       for (int i = 0; i < IPT; ++i) {
         const int r = i * RPI + lane / CPR, c = lane % CPR;
         const int j = min(j0 + r, T_in - 1);
-        const __bf16* row = (j < d.len_in) ? k_cache + (d.in_off + j) * D
-                                           : k_new + ((int64_t)d.unit * N_k + (j - d.len_in)) * D;
+        const __bf16* row = (j < it.len_in) ? k_cache + (it.in_off + j) * D
+                                            : k_new + ((int64_t)it.unit * N_k + (j - it.len_in)) * D;
         score_dma16(row + ((c ^ score_swz<D>(r)) & (CPR - 1)) * 8, dst + i * 1024);
       }
     }
   };
-  issue(0);
+  if (n_tiles > 0) issue(0);
 
   // Q~ fragments (rows beyond n_obs are zero and get zero weight below).
   bf16x8 qf[KK];
   {
     const bool qv = col < n_obs;
-    const __bf16* qrow = q + ((int64_t)d.unit * N_k + (qv ? q_rows[col] : 0)) * D;
+    const __bf16* qrow = q + ((int64_t)it.unit * N_k + (qv ? q_rows[col] : 0)) * D;
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) {
       bf16x8 z = {0};
       qf[kk] = qv ? *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * half) : z;
     }
   }
-  const double c2 = (double)scale * kLog2e;  // logits in log2 units: t = dot * c2
-
-  double m_i[16], w_i[16];
-  if (PASS == 2) {
-    // lane col (both halves) folds row col, then every lane fetches its 16 rows
-    const double l = sum_unit[col];
-    int ex;
-    (void)frexp(l, &ex);                       // l = f * 2^ex, f in [0.5, 1)
-    const double mm = (double)ex;
-    const double ww = (col < n_obs) ? ldexp(1.0, ex) / l : 0.0;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int src = c_row(r, half);
-      m_i[r] = __hiloint2double(__shfl(__double2hiint(mm), src, 64), __shfl(__double2loint(mm), src, 64));
-      w_i[r] = __hiloint2double(__shfl(__double2hiint(ww), src, 64), __shfl(__double2loint(ww), src, 64));
-    }
-  }
-  // everything the compiler loaded itself must have landed before the loop, so
-  // that no compiler-placed vmcnt wait inside it also drains the tile copies
+  const double c2 = (double)scale * kLog2e * kFixOne;  // logits in log2 units, fixed point: t * 2^22 = dot * c2
+  // everything the compiler loaded itself must have landed before the tiles are
+  // consumed, so that no compiler-placed vmcnt wait also drains the tile copies
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) asm volatile("" ::"v"(qf[kk]));
-  if (PASS == 2) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) asm volatile("" ::"v"(m_i[r]), "v"(w_i[r]));
-  }
 
-  double lsum[16];
-#pragma unroll
-  for (int r = 0; r < 16; ++r) lsum[r] = 0.0;
   int k_off[KK];
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) k_off[kk] = col * D + (((2 * kk + half) ^ score_swz<D>(col)) & (CPR - 1)) * 8;
 
-  for (int t = 0; t < n_tiles; ++t) {
-    if (t + 1 < n_tiles) {
-      issue(t + 1);
-      score_wait_vm<IPT>();   // tile t has landed, tile t+1 stays in flight
-    } else {
-      score_wait_vm<0>();
-    }
-    const __bf16* Kt = &tiles[w][t & 1][0];
-    // Raw dot products: every MFMA covers 16 head-dim elements and starts from a
-    // zero accumulator; the slice results are summed in fp64, so float32 rounding
-    // only ever acts on partial sums that are small next to the full dot product.
-    double sd[16];
+  // ---- A: logits of the item's tiles ---------------------------------------
+  int tq[kItemTiles][16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) sd[r] = 0.0;
-#pragma unroll
-    for (int kk = 0; kk < KK; ++kk) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Kt[k_off[kk]]);
-      floatx16 c = {0};
-      c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], kf, c, 0, 0, 0);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) sd[r] += (double)c[r];
-    }
-    const int j = key0 + t * 32 + col;
-    const bool valid = j < T_in;
-    if (PASS == 1) {
-      if (valid) {
-#pragma unroll
-        for (int r = 0; r < 16; ++r) lsum[r] += exp2_wide(sd[r] * c2);
+  for (int t = 0; t < kItemTiles; ++t) {
+    if (t < n_tiles) {                 // wave-uniform
+      if (t + 1 < n_tiles) {
+        issue(t + 1);
+        score_wait_vm<IPT>();          // tile t has landed, tile t+1 stays in flight
+      } else {
+        score_wait_vm<0>();
       }
-    } else {
-      double imp = 0.0;
+      const __bf16* Kt = &tiles[w][t & 1][0];
+      // Raw dot products: every MFMA covers 16 head-dim elements and starts from a
+      // zero accumulator; the slice results are summed in fp64, so float32 rounding
+      // only ever acts on partial sums that are small next to the full dot product.
+      double sd[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) imp = fma((double)exp2_split(fma(sd[r], c2, -m_i[r])), w_i[r], imp);
-      imp += shfl_xor_f64(imp, 32);
-      if (valid && half == 0) importance[(int64_t)d.unit * imp_stride + j] = (float)imp;
+      for (int r = 0; r < 16; ++r) sd[r] = 0.0;
+#pragma unroll
+      for (int kk = 0; kk < KK; ++kk) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Kt[k_off[kk]]);
+        floatx16 c = {0};
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], kf, c, 0, 0, 0);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sd[r] += (double)c[r];
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) tq[t][r] = fix_from(sd[r] * c2);
+    } else {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) tq[t][r] = 0;
     }
   }
 
-  if (PASS == 1) {
-    // lanes of a half-wave hold different keys of the same 16 query rows
+  // ---- B: row sums -> unit normalisers, then announce arrival ---------------
+  // The four waves of a work-group hold items of the same unit.  Each wave's
+  // tile buffers are free by now, so they carry the exchange: every wave leaves
+  // its 32 row sums there, wave 0 adds the four and sends one atomic per row.
+  // The atomics return their old value: once it is back the add has been
+  // performed, so the arrival that follows is ordered after the contributions.
+  double* red = reinterpret_cast<double*>(&tiles[w][0][0]);
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const double l = half_sum_f64(lsum[r]);
-      if (col == 0) atomicAdd(&sum_unit[c_row(r, half)], l);
+  for (int r = 0; r < 16; ++r) {
+    double lsum = 0.0;
+#pragma unroll
+    for (int t = 0; t < kItemTiles; ++t)
+      if (t < n_tiles && key0 + t * 32 + col < T_in) lsum += exp2_fix(tq[t][r]);
+    const double l = half_sum_f64(lsum);
+    if (col == 0) red[c_row(r, half)] = l;
+  }
+  __syncthreads();
+  double* inv_s = reinterpret_cast<double*>(&tiles[0][0][0]) + 64;  // in wave 0's buffer, after its sums
+  int* ok_s = reinterpret_cast<int*>(inv_s + kMaxObs);
+  unsigned ticket = 0;
+  if (w == 0) {
+    if (lane < kMaxObs) {
+      double tot = 0.0;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) tot += reinterpret_cast<const double*>(&tiles[k][0][0])[lane];
+      const double old = atomicAdd(&sum_unit[lane], tot);
+      asm volatile("" ::"v"(old));
     }
-  } else {
-    // the wave that finishes the unit's last chunk cleans the workspace (every
-    // wave of the unit has read the row sums before it bumps the counter)
-    unsigned arrived = 0;
-    if (lane == 0) arrived = atomicAdd(&counters[it.pos], 1u);
-    arrived = __builtin_amdgcn_readfirstlane(arrived);
-    if ((int)arrived == n_chunks - 1) {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // ---- C: wait for the unit, read the normalisers -------------------------
+    int ok = 1;
+    if (lane == 0) {
+      unsigned seen = atomicAdd(&cnt[0], 1u) + 1u;
+      int polls = 0;
+      while (seen < (unsigned)it.n_groups) {
+        if (++polls > spin_limit) { ok = 0; break; }
+        __builtin_amdgcn_s_sleep(16);
+        seen = atomicAdd(&cnt[0], 0u);   // read-modify-write: always served at the coherence point
+      }
+    }
+    ok = __builtin_amdgcn_readfirstlane(ok);
+    if (ok) {
+      if (lane < kMaxObs) {
+        const double l = atomicAdd(&sum_unit[lane], 0.0);
+        inv_s[lane] = (lane < n_obs) ? 1.0 / l : 0.0;
+      }
+      // the read is back before the ticket is drawn: whoever draws the last
+      // ticket may clear the sums without racing any reader
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      if (lane == 0) ticket = atomicAdd(&cnt[1], 1u);
+    } else if (lane == 0) {
+      __hip_atomic_store(fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    if (lane == 0) *ok_s = ok;
+  }
+  __syncthreads();
+  if (*ok_s == 0) return;
+  double inv_r[16];
+#pragma unroll
+  for (int r = 0; r < 16; ++r) inv_r[r] = inv_s[c_row(r, half)];
+
+#pragma unroll
+  for (int t = 0; t < kItemTiles; ++t) {
+    if (t < n_tiles) {
+      double imp = 0.0;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) imp = fma(exp2_fix(tq[t][r]), inv_r[r], imp);
+      imp += shfl_xor_f64(imp, 32);
+      const int j = key0 + t * 32 + col;
+      if (j < T_in && half == 0) importance[(int64_t)it.unit * imp_stride + j] = (float)imp;
+    }
+  }
+  if (w == 0) {
+    // the wave that drew a unit's last ticket leaves sums and counters zeroed for the next launch
+    ticket = __builtin_amdgcn_readfirstlane(ticket);
+    if ((int)ticket == it.n_groups - 1) {
       if (lane < kMaxObs) sum_unit[lane] = 0.0;
-      if (lane == 0) counters[it.pos] = 0;
+      if (lane < 2) cnt[lane] = 0;
     }
   }
 }
@@ -444,46 +463,49 @@ void launch_generic(hipStream_t s, dim3 grid, const UnitDesc* descs, const int32
                      stats, importance, imp_stride);
 }
 
-template <int D>
-void launch_mfma(hipStream_t s, const UnitDesc* descs, const int32_t* list, const void* items, int n_items,
-                 int max_chunks, const void* q, const int32_t* q_rows, int n_obs, int N_k, float scale,
-                 const void* k_cache, const void* k_new, double* stats, double* rowstat, unsigned* counters,
-                 float* importance, int64_t imp_stride) {
-  typedef __bf16 T;
-  (void)stats;
-  dim3 grid((n_items + 3) / 4);
-  hipLaunchKernelGGL((score_mfma<D, 1>), grid, dim3(kThreads), 0, s, descs, list, (const ScoreItem*)items,
-                     n_items, max_chunks, (const T*)q, q_rows, n_obs, N_k, scale, (const T*)k_cache,
-                     (const T*)k_new, rowstat, counters, importance, imp_stride);
-  hipLaunchKernelGGL((score_mfma<D, 2>), grid, dim3(kThreads), 0, s, descs, list, (const ScoreItem*)items,
-                     n_items, max_chunks, (const T*)q, q_rows, n_obs, N_k, scale, (const T*)k_cache,
-                     (const T*)k_new, rowstat, counters, importance, imp_stride);
-}
-
 }  // namespace
 
 int score_item_keys(int dtype) { return dtype == 1 ? kScoreChunk : kItemKeys; }
 
-void launch_score(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, const int32_t* list,
-                  int n_list, int max_t_in, const void* items, int n_items, const void* q,
-                  const int32_t* q_rows, int n_obs, int N_k, float scale, const void* k_cache,
-                  const void* k_new, double* stats, double* rowstat, unsigned* counters, float* importance,
-                  int64_t imp_stride) {
+int score_fused_capacity(int head_dim) {
+  int dev = 0, cus = 0, blocks = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  const hipError_t e = head_dim == 64
+      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<64>, kThreads, 0)
+      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<128>, kThreads, 0);
+  if (e != hipSuccess) return 0;
+  return blocks * cus * (kThreads / 64);
+}
+
+void launch_score_fused(hipStream_t s, int head_dim, const ScoreItem* items, int n_items, const void* q,
+                        const int32_t* q_rows, int n_obs, int N_k, float scale, const void* k_cache,
+                        const void* k_new, double* rowsum, unsigned* counters, float* importance,
+                        int64_t imp_stride, int* fault, int spin_limit) {
+  if (n_items <= 0) return;
+  typedef __bf16 T;
+  dim3 grid((n_items + 3) / 4);
+  if (head_dim == 64)
+    hipLaunchKernelGGL(score_fused<64>, grid, dim3(kThreads), 0, s, items, n_items, (const T*)q, q_rows, n_obs,
+                       N_k, scale, (const T*)k_cache, (const T*)k_new, rowsum, counters, importance, imp_stride,
+                       fault, spin_limit);
+  else
+    hipLaunchKernelGGL(score_fused<128>, grid, dim3(kThreads), 0, s, items, n_items, (const T*)q, q_rows, n_obs,
+                       N_k, scale, (const T*)k_cache, (const T*)k_new, rowsum, counters, importance, imp_stride,
+                       fault, spin_limit);
+}
+
+void launch_score_generic(hipStream_t s, int head_dim, const UnitDesc* descs, const int32_t* list, int n_list,
+                          int max_t_in, const void* q, const int32_t* q_rows, int n_obs, int N_k, float scale,
+                          const void* k_cache, const void* k_new, double* stats, float* importance,
+                          int64_t imp_stride) {
   if (n_list <= 0 || max_t_in <= 0) return;
-  if (dtype == 1) {
-    const int max_chunks = (max_t_in + kScoreChunk - 1) / kScoreChunk;
-    dim3 grid(max_chunks, n_list);
+  const int max_chunks = (max_t_in + kScoreChunk - 1) / kScoreChunk;
+  dim3 grid(max_chunks, n_list);
 #define HACK_ARGS s, grid, descs, list, max_chunks, q, q_rows, n_obs, N_k, scale, k_cache, k_new, stats, importance, imp_stride
-    if (head_dim == 64) launch_generic<float, 64>(HACK_ARGS);
-    else launch_generic<float, 128>(HACK_ARGS);
+  if (head_dim == 64) launch_generic<float, 64>(HACK_ARGS);
+  else launch_generic<float, 128>(HACK_ARGS);
 #undef HACK_ARGS
-  } else {
-    const int max_chunks = (max_t_in + kItemKeys - 1) / kItemKeys;
-#define HACK_ARGS s, descs, list, items, n_items, max_chunks, q, q_rows, n_obs, N_k, scale, k_cache, k_new, stats, rowstat, counters, importance, imp_stride
-    if (head_dim == 64) launch_mfma<64>(HACK_ARGS);
-    else launch_mfma<128>(HACK_ARGS);
-#undef HACK_ARGS
-  }
 }
 
 }  // namespace hack

@@ -208,6 +208,43 @@ def test_score_matches_oracle(dtype, d, Nk, lens):
     hk.close()
 
 
+def test_score_many_units_split_into_launch_groups_and_repeated_calls():
+    """More score work items than the device holds at once: the library must cut
+    the launch into groups of whole units.  Calling twice on the same context
+    also checks that the normaliser workspace is left clean."""
+    u = _u()
+    rng = np.random.default_rng(5)
+    H, B, d, Nk, dtype = 16, 6, 128, 32, "bf16"
+    U = H * B
+    lens = [int(x) for x in rng.integers(3900, 4200, U)]
+    lens[7], lens[50] = 1, 130                                         # short units among long ones
+    hk = u.make_hack(heads=H, head_dim=d, dtype=dtype, max_units=U, max_cache_len=4352, max_queries=Nk)
+    scale = float(np.float32(1.0 / np.sqrt(d)))
+    rows = [(u.rand_values(rng, (n, d), dtype), None) for n in lens]
+    rows = [(k, k) for k, _ in rows]
+    cin, _ = u.build_cache(rows, d, dtype)
+    q = u.rand_values(rng, (B, H, Nk, d), dtype) * 2.0
+    k_new = u.rand_values(rng, (B, H, Nk, d), dtype)
+    stride = 4352
+    obs = ho.observation_rows(Nk, 32)
+    qd, kd = u.to_dev(q, dtype), u.to_dev(k_new, dtype)
+    for rep in range(2):
+        imp = torch.full((U, stride), -1.0, device=u.DEV)
+        hk.score(qd, cin, scale, imp, k_new=kd)
+        torch.cuda.synchronize()
+        got = imp.cpu().numpy().astype(np.float64)
+        T_all = np.array(lens) + Nk
+        sums = np.array([got[uu, :T_all[uu]].sum() for uu in range(U)])
+        assert np.all(np.abs(sums - len(obs)) < 1e-4 * len(obs)), (rep, sums.min(), sums.max())
+        for uu in (0, 7, 50, 51, U // 2, U - 1):
+            b, h = divmod(uu, H)
+            K_in = np.concatenate([rows[uu][0], k_new[b, h]]).astype(np.float64)
+            want = ho.importance(q[b, h][obs].astype(np.float64), K_in, scale)
+            assert float(np.max(np.abs(got[uu, :len(want)] - want) / want)) < 1e-6, (rep, uu)
+            assert np.all(got[uu, len(want):] == -1.0)
+    hk.close()
+
+
 def test_score_cache_only_custom_rows_and_inactive_units():
     u = _u()
     rng = np.random.default_rng(3)
