@@ -3,8 +3,8 @@
 // inside a scale step) on gfx950.
 //
 // bf16 path (flash-style, one pass over K/V with an online softmax):
-//   * work item = (unit, tile of 4 waves x NQB x 32 queries); K/V tiles of 64
-//     keys are staged once per work-group in LDS and shared by the four waves.
+//   * work item = (unit, tile of 4 waves x 32 queries); K/V blocks of 32 keys
+//     are staged once per work-group in LDS and shared by the four waves.
 //   * S^T = K Q^T with v_mfma_f32_32x32x16_bf16: the accumulator then holds,
 //     per lane, one query column and 16 key rows, so the softmax row reductions
 //     are in-lane plus one exchange with lane^32, and the running max / rescale
@@ -13,9 +13,12 @@
 //     B operand (C rows 8(r/4)+4h+r%4 of registers 8s..8s+7 are exactly two runs
 //     of four consecutive keys), and V^T comes from row-major V in LDS through
 //     the transposing LDS read (ds_read_b64_tr_b16), four keys per read.
-//   * K/V tiles are double-buffered and loaded HBM -> LDS directly (no register
-//     round trip), one barrier per tile; an XOR swizzle of 16-byte chunks keeps
-//     the b128 K reads and the transposing V reads bank-conflict free.
+//   * the loop runs over 32-key blocks, software-pipelined by one block: the
+//     scores of block b+1 are formed while block b is exponentiated.
+//   * K/V blocks travel HBM -> LDS directly (no register round trip) through a
+//     ring of four slots per tensor, one barrier per block; an XOR swizzle of
+//     16-byte chunks keeps the b128 K reads and the transposing V reads
+//     bank-conflict free.
 // fp32 path: one query per lane, fp32 FMA, K/V rows broadcast from LDS; exact
 // enough for the 1e-4 bar and only used for the small fp32 configuration.
 #include <type_traits>
@@ -99,7 +102,7 @@ __global__ __launch_bounds__(kGenQ) void attn_generic(
 // ---------------------------------------------------------------------------
 // bf16 MFMA path
 // ---------------------------------------------------------------------------
-constexpr int kKT = 64;      // keys per LDS tile
+constexpr int kKB = 32;      // keys per block (one LDS ring slot)
 constexpr float kRescaleAbove = 65536.f;  // a block sum of probabilities at or above this moves the reference
 
 __device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
@@ -155,8 +158,19 @@ __device__ __forceinline__ float pair_sum(float v) {
 
 // NW waves per work-group, each wave owns 32 queries; two work-groups share a CU.
 //
-// The vector ALU is the scarce unit here (per 32-key block a wave issues 16 MFMAs
-// but also has to exponentiate 16 scores per lane), so the softmax is kept to
+// The loop runs over 32-key blocks and is software-pipelined by one block: while
+// the vector ALU turns the scores of block b into probabilities, the matrix core
+// already forms the scores of block b+1; then O^T += V^T P^T for block b.  (A
+// wave issues in order, so matrix and vector work only overlap if independent
+// instructions of both kinds sit next to each other in its own stream; on this
+// chip ~4 simple VALU ops or ~2 exponentials hide under one 32x32x16 MFMA.)
+// K and V blocks travel HBM -> LDS through two rings of kRing slots: the copy of
+// block b+3 is issued at stage b into the slot block b-1 has just left, so a
+// copy has two full stages to land and one barrier per stage both publishes
+// block b+1 and frees the slot.
+//
+// The vector ALU is the scarce unit (per block a wave issues 16 MFMAs but also
+// has to exponentiate 16 scores per lane), so the softmax is kept to
 // fma + exp2 + bf16 pack + a bf16 dot2 for the row sum:
 //   * the running reference m_run is only moved when a probability would leave
 //     [0, 2^16): the exponentials are formed optimistically against the current
@@ -164,6 +178,14 @@ __device__ __forceinline__ float pair_sum(float v) {
 //     in the very first block) is the max computed and everything rescaled;
 //   * the row sum is taken over the bf16-rounded probabilities, the same numbers
 //     the PV product uses.
+constexpr int kRing = 4;     // LDS ring slots per tensor (32-key blocks)
+
+template <int N> __device__ __forceinline__ void dma_wait_but() {
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
+
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
     const UnitDesc* __restrict__ descs, const AttnItem* __restrict__ items,
@@ -173,9 +195,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
   constexpr int KK = D / 16;        // MFMA steps over head_dim for S^T
   constexpr int MB = D / 32;        // 32-row blocks of O^T
   constexpr int CPR = D / 8;        // 16-byte chunks per row
-  constexpr int RPI = 64 / CPR;     // tile rows covered by one wave-wide load instruction
-  constexpr int IPW = (kKT / RPI) / NW;  // load instructions per wave, tile and tensor
-  constexpr int TILE_ELEMS = kKT * D;
+  constexpr int RPI = 64 / CPR;     // block rows covered by one wave-wide copy instruction
+  constexpr int IPW = (kKB / RPI) / NW;  // copy instructions per wave, block and tensor
+  constexpr int BLK = kKB * D;      // elements per block and tensor
+  static_assert(IPW >= 1, "a block must give every wave at least one copy instruction");
 
   const AttnItem it = items[blockIdx.x];
   if (it.desc < 0) return;
@@ -185,8 +208,51 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
 
-  __shared__ __attribute__((aligned(1024))) __bf16 Ks[2][TILE_ELEMS];
-  __shared__ __attribute__((aligned(1024))) __bf16 Vs[2][TILE_ELEMS];
+  __shared__ __attribute__((aligned(1024))) __bf16 Ks[kRing][BLK];
+  __shared__ __attribute__((aligned(1024))) __bf16 Vs[kRing][BLK];
+
+  const __bf16* kg = k_cache + d.out_off * D;
+  const __bf16* vg = v_cache + d.out_off * D;
+  const int n_blocks = (len + kKB - 1) / kKB;
+
+  // Block copies.  Lane l of copy instruction i of this wave fills LDS row
+  // r = (w + i NW) RPI + l / CPR, chunk position c = l % CPR, from global chunk
+  // c ^ f(r) of block row r; the byte offsets inside a full block are loop invariant.
+  unsigned k_src[IPW], v_src[IPW];
+#pragma unroll
+  for (int i = 0; i < IPW; ++i) {
+    const int r = (w + i * NW) * RPI + lane / CPR, c = lane % CPR;
+    k_src[i] = (unsigned)(r * D + ((c ^ swz_k<D>(r)) & (CPR - 1)) * 8) * 2u;
+    v_src[i] = (unsigned)(r * D + ((c ^ swz_v<D>(r)) & (CPR - 1)) * 8) * 2u;
+  }
+  const unsigned ks_lds = lds_addr_of(&Ks[0][0]), vs_lds = lds_addr_of(&Vs[0][0]);
+  // Rows past the end of a ragged last block repeat the last valid row (finite
+  // data); their scores are masked to -inf, so their probabilities are exactly 0.
+  auto issue = [&](int b, int slot) {
+    const int t0 = b * kKB;
+    const __bf16* kb = kg + (int64_t)t0 * D;
+    const __bf16* vb = vg + (int64_t)t0 * D;
+    if (t0 + kKB <= len) {
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        const unsigned dst = (unsigned)((slot * BLK + (w + i * NW) * 512) * 2);
+        load_to_lds(kb, k_src[i], ks_lds + dst);
+        load_to_lds(vb, v_src[i], vs_lds + dst);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        const int r = (w + i * NW) * RPI + lane / CPR, c = lane % CPR;
+        const int rc = min(r, len - 1 - t0);
+        const unsigned dst = (unsigned)((slot * BLK + (w + i * NW) * 512) * 2);
+        load_to_lds(kb, (unsigned)(rc * D + ((c ^ swz_k<D>(r)) & (CPR - 1)) * 8) * 2u, ks_lds + dst);
+        load_to_lds(vb, (unsigned)(rc * D + ((c ^ swz_v<D>(r)) & (CPR - 1)) * 8) * 2u, vs_lds + dst);
+      }
+    }
+  };
+  issue(0, 0);
+  if (n_blocks > 1) issue(1, 1);
+  if (n_blocks > 2) issue(2, 2);
 
   // Q fragments (B operand of S^T = K Q^T): query col, head-dim slice [16kk + 8h, +8).
   const int q0 = it.q_tile * (NW * 32) + w * 32;
@@ -197,7 +263,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * half);
     // Consume the fragments here so that their loads are waited for before the
-    // main loop: a vmcnt wait inside the loop would also drain the tile copies
+    // main loop: a vmcnt wait inside the loop would also drain the block copies
     // that are meant to stay in flight.
 #pragma unroll
     for (int kk = 0; kk < KK; ++kk) asm volatile("" ::"v"(qf[kk]));
@@ -212,68 +278,23 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
   const float c2 = scale * kLog2eF;
   float mc = -INFINITY;   // m_run * c2
 
-  const __bf16* kg = k_cache + d.out_off * D;
-  const __bf16* vg = v_cache + d.out_off * D;
-
-  // Tile copies.  Lane l of load instruction i of this wave fills LDS row
-  // r = (w + i NW) RPI + l / CPR, chunk position c = l % CPR, from global chunk
-  // c ^ f(r) of tile row r; the byte offsets inside a full tile are loop invariant.
-  unsigned k_src[IPW], v_src[IPW];
-#pragma unroll
-  for (int i = 0; i < IPW; ++i) {
-    const int r = (w + i * NW) * RPI + lane / CPR, c = lane % CPR;
-    k_src[i] = (unsigned)(r * D + ((c ^ swz_k<D>(r)) & (CPR - 1)) * 8) * 2u;
-    v_src[i] = (unsigned)(r * D + ((c ^ swz_v<D>(r)) & (CPR - 1)) * 8) * 2u;
-  }
-  const unsigned ks_lds = lds_addr_of(&Ks[0][0]), vs_lds = lds_addr_of(&Vs[0][0]);
-  auto issue_full = [&](int t0, int buf) {
-    const __bf16* kb = kg + (int64_t)t0 * D;
-    const __bf16* vb = vg + (int64_t)t0 * D;
-#pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-      const unsigned dst = (unsigned)((buf * TILE_ELEMS + (w + i * NW) * 512) * 2);
-      load_to_lds(kb, k_src[i], ks_lds + dst);
-      load_to_lds(vb, v_src[i], vs_lds + dst);
-    }
-  };
-  // Ragged last tile: rows past the end repeat the last valid row (finite data);
-  // their scores are masked to -inf, so their probabilities are exactly 0.
-  auto issue_tail = [&](int t0, int buf) {
-    const __bf16* kb = kg + (int64_t)t0 * D;
-    const __bf16* vb = vg + (int64_t)t0 * D;
-#pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-      const int r = (w + i * NW) * RPI + lane / CPR, c = lane % CPR;
-      const int rc = min(r, len - 1 - t0);
-      const unsigned dst = (unsigned)((buf * TILE_ELEMS + (w + i * NW) * 512) * 2);
-      load_to_lds(kb, (unsigned)(rc * D + ((c ^ swz_k<D>(r)) & (CPR - 1)) * 8) * 2u, ks_lds + dst);
-      load_to_lds(vb, (unsigned)(rc * D + ((c ^ swz_v<D>(r)) & (CPR - 1)) * 8) * 2u, vs_lds + dst);
-    }
-  };
-  auto issue = [&](int t0, int buf) {
-    if (t0 + kKT <= len) issue_full(t0, buf);
-    else issue_tail(t0, buf);
-  };
-  // per-lane LDS element offsets of the operand reads (tile-relative); everything
-  // else in an LDS address is a compile-time immediate (buffer, key block, sg)
-  int k_off[KK];           // K operand: row col (+32 kb), chunk 2kk + half
+  // per-lane LDS element offsets of the operand reads (block-relative); the ring
+  // slot is a compile-time immediate
+  int k_off[KK];           // K operand: row col, chunk 2kk + half
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) k_off[kk] = col * D + (((2 * kk + half) ^ swz_k<D>(col)) & (CPR - 1)) * 8;
   const int g = lane >> 4, e = (lane >> 2) & 3, qd = lane & 3;
-  int v_off[MB];           // V^T operand: row 4 half + e (+16 sg, +32 kb, +8), head-dim 32mb + 16(g&1) + 4qd
+  int v_off[MB];           // V^T operand: row 4 half + e (+16 sg, +8), head-dim 32mb + 16(g&1) + 4qd
 #pragma unroll
   for (int mb = 0; mb < MB; ++mb)
     v_off[mb] = (4 * half + e) * D + (((4 * mb + 2 * (g & 1) + (qd >> 1)) ^ swz_v<D>(e)) & (CPR - 1)) * 8 + 4 * (qd & 1);
 
   const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
 
-  // One 32-key block of the tile in buffer BUF: S^T, softmax, O^T update.
-  auto block = [&](auto buf_tag, auto kb_tag, auto tail_tag, int t0) {
-    constexpr int BUF = decltype(buf_tag)::value;
-    constexpr int KB = decltype(kb_tag)::value;
-    const __bf16* Kt = &Ks[BUF][KB * 32 * D];
-    const __bf16* Vt = &Vs[BUF][KB * 32 * D];
-    // ---- S^T block: 32 keys x 32 queries ----
+  // S^T of block b (32 keys x 32 queries) from ring slot SLOT.
+  auto scores = [&](auto slot_tag, int b) -> floatx16 {
+    constexpr int SLOT = decltype(slot_tag)::value;
+    const __bf16* Kt = &Ks[SLOT][0];
     floatx16 sc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sc[r] = 0.f;
@@ -282,16 +303,21 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
       const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Kt[k_off[kk]]);
       sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sc, 0, 0, 0);
     }
-    if (decltype(tail_tag)::value) {   // ragged end: keys past the end get -inf
+    return sc;
+  };
+  // ragged end: keys past the end get -inf
+  auto mask_tail = [&](floatx16& sc, int b) {
+    if ((b + 1) * kKB > len) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int key = t0 + KB * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+        const int key = b * kKB + 8 * (r >> 2) + 4 * half + (r & 3);
         if (key >= len) sc[r] = -INFINITY;
       }
     }
-    // ---- probabilities against the current reference (per lane: one query, 16
-    //      keys; the partner lane l ^ 32 holds the other 16) ----
-    bf16x8 pf[2];
+  };
+  // probabilities of a block against the current reference (per lane: one query,
+  // 16 keys; the partner lane l ^ 32 holds the other 16) and their sum
+  auto probs = [&](const floatx16& sc, bf16x8 (&pf)[2]) -> float {
     float psum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) pf[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[r], c2, -mc));
@@ -300,34 +326,31 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
       const bf16x2 pr = {pf[r >> 3][r & 7], pf[r >> 3][(r & 7) + 1]};
       psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, psum, false);
     }
-    if (__any(!(psum < kRescaleAbove))) {
-      // Some probability left the safe range (always so in the first block, where
-      // the reference is -inf): move the reference to the running max, bring the
-      // accumulators to the new scale and redo this block's probabilities.
-      float mx = sc[0];
+    return psum;
+  };
+  // Some probability left the safe range (always so in the first block, where the
+  // reference is -inf): move the reference to the running max, bring the
+  // accumulators to the new scale and redo this block's probabilities.
+  auto rescale = [&](const floatx16& sc, bf16x8 (&pf)[2]) -> float {
+    float mx = sc[0];
 #pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
-      mx = pair_max(mx);
-      const float m_new = fmaxf(m_run, mx);   // finite: the block holds a valid key
-      const float a = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-      l_run *= a;
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
+    mx = pair_max(mx);
+    const float m_new = fmaxf(m_run, mx);   // finite: the block holds a valid key
+    const float a = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+    l_run *= a;
 #pragma unroll
-      for (int mb = 0; mb < MB; ++mb)
+    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) o[mb][r] *= a;
-      m_run = m_new;
-      mc = m_new * c2;
-      psum = 0.f;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) pf[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[r], c2, -mc));
-#pragma unroll
-      for (int r = 0; r < 16; r += 2) {
-        const bf16x2 pr = {pf[r >> 3][r & 7], pf[r >> 3][(r & 7) + 1]};
-        psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, psum, false);
-      }
-    }
-    l_run += psum;
-    // ---- O^T += V^T P^T ----
+      for (int r = 0; r < 16; ++r) o[mb][r] *= a;
+    m_run = m_new;
+    mc = m_new * c2;
+    return probs(sc, pf);
+  };
+  // O^T += V^T P^T for the block in ring slot SLOT
+  auto pv = [&](auto slot_tag, const bf16x8 (&pf)[2]) {
+    constexpr int SLOT = decltype(slot_tag)::value;
+    const __bf16* Vt = &Vs[SLOT][0];
 #pragma unroll
     for (int sg = 0; sg < 2; ++sg) {
 #pragma unroll
@@ -346,37 +369,74 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
     }
   };
 
-  using K0 = std::integral_constant<int, 0>;
-  using K1 = std::integral_constant<int, 1>;
-  using B0 = std::integral_constant<int, 0>;
-  using B1 = std::integral_constant<int, 1>;
-  const int n_tiles = (len + kKT - 1) / kKT;
-  const int n_full = len / kKT;       // tiles without a ragged end
-  // One tile: start the copy of the next one, consume this one, publish the next.
-  auto tile = [&](auto buf_tag, auto tail_tag, int t) {
-    constexpr int BUF = decltype(buf_tag)::value;
+  // Stage b (ring slot S = b % kRing): sc holds the scores of block b on entry
+  // and those of block b+1 on exit.  LAST: block b is the unit's last one.
+  // TAIL: block b+1 may be the ragged last block (its scores then need the mask,
+  // whose branch would keep the scheduler from mixing matrix and vector work).
+  auto stage = [&](auto slot_tag, auto last_tag, auto tail_tag, int b, floatx16& sc) {
+    constexpr int S = decltype(slot_tag)::value;
+    constexpr bool LAST = decltype(last_tag)::value;
     constexpr bool TAIL = decltype(tail_tag)::value;
-    const int t0 = t * kKT;
-    if (t + 1 < n_tiles) issue(t0 + kKT, BUF ^ 1);   // lands while this tile is consumed
-    block(buf_tag, K0{}, tail_tag, t0);
-    if (!TAIL || t0 + 32 < len) block(buf_tag, K1{}, tail_tag, t0);
-    dma_wait_all();
-    __syncthreads();  // next tile has landed for every wave; this tile is free to overwrite
+    using S1 = std::integral_constant<int, (S + 1) % kRing>;
+    // everything but the copy group issued one stage ago (block b+2) has landed
+    if (b + 2 < n_blocks) dma_wait_but<2 * IPW>();
+    else dma_wait_but<0>();
+    __syncthreads();   // block b+1 is visible to every wave; the slot of block b-1 is free
+    if (b + 3 < n_blocks) issue(b + 3, (S + 3) % kRing);
+    __builtin_amdgcn_sched_barrier(0);
+    floatx16 sn;
+    if (!LAST) sn = scores(S1{}, b + 1);
+    bf16x8 pf[2];
+    float psum = probs(sc, pf);
+    if (!LAST) {
+      // the K fragment reads first, then one MFMA of the next block's scores and a
+      // slice of this block's softmax arithmetic, and so on
+      __builtin_amdgcn_sched_group_barrier(0x100, KK, 0);
+#pragma unroll
+      for (int i = 0; i < KK; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 48 / KK, 0);
+      }
+    }
+    if (!LAST && TAIL) mask_tail(sn, b + 1);
+    if (__any(!(psum < kRescaleAbove))) psum = rescale(sc, pf);
+    l_run += psum;
+    pv(slot_tag, pf);
+    if (!LAST) sc = sn;
   };
 
-  issue(0, 0);
-  dma_wait_all();
+  using R0 = std::integral_constant<int, 0>;
+  using R1 = std::integral_constant<int, 1>;
+  using R2 = std::integral_constant<int, 2>;
+  using R3 = std::integral_constant<int, 3>;
+  using No = std::false_type;
+  using Yes = std::true_type;
+
+  // block 0 has landed -> its scores
+  if (n_blocks > 2) dma_wait_but<4 * IPW>();
+  else if (n_blocks > 1) dma_wait_but<2 * IPW>();
+  else dma_wait_but<0>();
   __syncthreads();
-  int t = 0;
-  for (; t + 2 <= n_full; t += 2) {
-    tile(B0{}, std::false_type{}, t);
-    tile(B1{}, std::false_type{}, t + 1);
+  floatx16 sc = scores(R0{}, 0);
+  mask_tail(sc, 0);
+
+  // main loop: four stages whose next blocks are all full
+  int b = 0;
+  for (; b + 5 < n_blocks; b += 4) {
+    stage(R0{}, No{}, No{}, b, sc);
+    stage(R1{}, No{}, No{}, b + 1, sc);
+    stage(R2{}, No{}, No{}, b + 2, sc);
+    stage(R3{}, No{}, No{}, b + 3, sc);
   }
-  if (t < n_full) {
-    tile(B0{}, std::false_type{}, t);
-    if (n_tiles > n_full) tile(B1{}, std::true_type{}, t + 1);
-  } else if (n_tiles > n_full) {
-    tile(B0{}, std::true_type{}, t);
+  // the remaining 1..5 blocks, one stage at a time (b is a multiple of 4 here)
+  for (; b < n_blocks; ++b) {
+    const bool last = (b + 1 == n_blocks);
+    switch (b & 3) {
+      case 0: if (last) stage(R0{}, Yes{}, Yes{}, b, sc); else stage(R0{}, No{}, Yes{}, b, sc); break;
+      case 1: if (last) stage(R1{}, Yes{}, Yes{}, b, sc); else stage(R1{}, No{}, Yes{}, b, sc); break;
+      case 2: if (last) stage(R2{}, Yes{}, Yes{}, b, sc); else stage(R2{}, No{}, Yes{}, b, sc); break;
+      default: if (last) stage(R3{}, Yes{}, Yes{}, b, sc); else stage(R3{}, No{}, Yes{}, b, sc); break;
+    }
   }
 
   // ---- normalise and store: lane holds query col, head-dim rows 32mb + 8(r/4) + 4h + r%4 ----
