@@ -86,6 +86,19 @@ void hack_destroy(hack_ctx* ctx);
 const char* hack_strerror(hack_status s);
 /* Message of the last failing call on ctx (valid until the next call). */
 const char* hack_last_error(const hack_ctx* ctx);
+/* Reports what kernels of earlier calls on ctx found while they ran (the calls
+ * themselves are asynchronous and had already returned HACK_OK).  Meaningful
+ * once the caller has synchronised the streams it used; every other entry
+ * point performs the same check first and fails the same way.
+ *   HACK_EUNSUPPORTED  a bf16 hack_score / hack_step met a logit
+ *                      |scale * q.k| > 354: its importance was formed with that
+ *                      logit clamped and may differ from the definition.
+ *                      Reported once, the context stays usable.
+ *   HACK_EHIP          a score kernel gave up its bounded wait for the other
+ *                      work-groups of a unit (the device did not keep the
+ *                      launch resident): its output is incomplete and the
+ *                      context must be destroyed. */
+hack_status hack_check(hack_ctx* ctx);
 
 /* ---- a1: importance estimation by subset attention --------------------
  * Sec. 4.4, "Importance Estimation via Efficient Subset Attention":
@@ -100,6 +113,11 @@ const char* hack_last_error(const hack_ctx* ctx);
  *   active   HOST [B*H] nonzero = score this unit, or NULL = all units
  *   importance DEVICE float [B*H, imp_stride]; row u receives T_in[u] values
  *            (rows of inactive units are left untouched)
+ * Accuracy (bf16): importance is within 1e-6 relative of the exact value while
+ * |scale * q.k| stays below ~40, and within 2.5e-8 * max|scale * q.k| beyond.
+ * Logits are supported up to |scale * q.k| <= 354 (far beyond what a float32
+ * importance can resolve); larger ones are clamped and reported by hack_check /
+ * the next call.
  * Errors: HACK_EINVAL (NULL/misaligned pointers, n_obs out of range, a q_idx
  * outside [0, N_k), offsets outside the cache), HACK_ECAPACITY (B*H, N_k or a
  * T_in above the context's limits, imp_stride < max T_in). */

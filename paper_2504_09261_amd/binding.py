@@ -19,7 +19,7 @@ HACK_BF16, HACK_F32 = 0, 1
 CONTEXTUAL, STRUCTURAL = 0, 1
 
 EXPORTS = [
-    "hack_create", "hack_destroy", "hack_strerror", "hack_last_error",
+    "hack_create", "hack_destroy", "hack_strerror", "hack_last_error", "hack_check",
     "hack_score", "hack_select", "hack_compact", "hack_attn",
     "hack_kvcache_rows_required", "hack_kvcache_create", "hack_kvcache_destroy",
     "hack_kvcache_reset", "hack_kvcache_view", "hack_step",
@@ -68,6 +68,7 @@ def load_library() -> C.CDLL:
     lib.hack_strerror.restype = C.c_char_p
     lib.hack_last_error.argtypes = [vp]
     lib.hack_last_error.restype = C.c_char_p
+    lib.hack_check.argtypes = [vp]
     lib.hack_score.argtypes = [vp, i32, i32, vp, pi32, i32, f32, pcache, vp, pu8, vp, i64, vp]
     lib.hack_select.argtypes = [vp, i32, vp, i64, pi32, pu8, pi32, i32, i32, vp, i64, pi32, vp]
     lib.hack_compact.argtypes = [vp, i32, i32, pcache, vp, vp, i32, vp, i64, pcache, vp]
@@ -207,6 +208,10 @@ class Hack:
     def _check(self, st: int):
         if st != 0:
             raise HackError(st, f"{self.lib.hack_strerror(st).decode()}: {self.lib.hack_last_error(self.ctx).decode()}")
+
+    def check(self):
+        """Raise if a kernel of an earlier call reported a problem (synchronise first)."""
+        self._check(self.lib.hack_check(self.ctx))
 
     # ---- a1 ----
     def score(self, q, cache: Cache, scale: float, importance, k_new=None, q_idx=None, n_obs: Optional[int] = None,

@@ -44,7 +44,8 @@ struct hack_ctx {
   double* stats = nullptr;       // fp32 path: [max_units, max_chunks, 32, 2] softmax partials
   double* rowstat = nullptr;     // bf16 path: [max_units, 32] softmax normalisers, zero between launches
   unsigned* counters = nullptr;  // bf16 path: [max_units, 2] arrival / reader counters, zero between launches
-  int* fault = nullptr;          // pinned, device-visible: set by a score wave whose bounded wait gave up
+  int* fault = nullptr;          // pinned, device-visible int[2]: [0] a score wave's bounded wait gave up (fatal),
+                                 // [1] a logit exceeded the range the bf16 score kernel supports
   int score_capacity = 0;        // bf16 path: score items one launch may hold (resident waves)
   int64_t ws_stride = 0;
   int max_chunks = 0;
@@ -171,11 +172,24 @@ void plan_select(int type, int T, int b, int n_init, int n_recent, UnitDesc* d) 
   }
 }
 
-hack_status check_common(hack_ctx* ctx, int32_t B, int32_t N_k, bool need_nk) {
-  if (!ctx) return HACK_EINVAL;
-  if (ctx->fault && *(volatile int*)ctx->fault)
+// Conditions that kernels of earlier calls found on the device.
+hack_status device_report(hack_ctx* ctx) {
+  volatile int* f = ctx->fault;
+  if (f && f[0])
     return fail(ctx, HACK_EHIP, "an earlier score launch gave up waiting for a unit's work items; its importance "
                                 "output is incomplete and this context is no longer usable");
+  if (f && f[1]) {
+    f[1] = 0;
+    return fail(ctx, HACK_EUNSUPPORTED, "an earlier bf16 score launch met a logit beyond +-354 (scale * q.k); such logits "
+                                        "are clamped, so its importance may differ from the definition");
+  }
+  return HACK_OK;
+}
+
+hack_status check_common(hack_ctx* ctx, int32_t B, int32_t N_k, bool need_nk) {
+  if (!ctx) return HACK_EINVAL;
+  const hack_status dev = device_report(ctx);
+  if (dev != HACK_OK) return dev;
   if (B < 1) return fail(ctx, HACK_EINVAL, "B must be >= 1 (got %d)", B);
   if ((int64_t)B * ctx->cfg.heads > ctx->cfg.max_units)
     return fail(ctx, HACK_ECAPACITY, "B*H = %lld exceeds max_units %d", (long long)B * ctx->cfg.heads, ctx->cfg.max_units);
@@ -287,6 +301,11 @@ extern "C" const char* hack_strerror(hack_status s) {
 
 extern "C" const char* hack_last_error(const hack_ctx* ctx) { return ctx ? ctx->err.c_str() : "NULL context"; }
 
+extern "C" hack_status hack_check(hack_ctx* ctx) {
+  if (!ctx) return HACK_EINVAL;
+  return device_report(ctx);
+}
+
 extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (!out || !cfg) return HACK_EINVAL;
   *out = nullptr;
@@ -309,8 +328,8 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->rowstat, (size_t)cfg->max_units * kMaxObs * 2 * sizeof(double));
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, (size_t)cfg->max_units * 2 * sizeof(unsigned));
   if (e == hipSuccess) e = hipMemset(ctx->counters, 0, (size_t)cfg->max_units * 2 * sizeof(unsigned));
-  if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->fault, sizeof(int), hipHostMallocDefault);
-  if (e == hipSuccess) *ctx->fault = 0;
+  if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->fault, 2 * sizeof(int), hipHostMallocDefault);
+  if (e == hipSuccess) ctx->fault[0] = ctx->fault[1] = 0;
   if (e == hipSuccess) e = hipMemset(ctx->rowstat, 0, (size_t)cfg->max_units * kMaxObs * 2 * sizeof(double));
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->arena_dev, kArenaBytes);

@@ -61,7 +61,8 @@ void launch_move(hipStream_t s, int elem_bytes, int head_dim, const UnitDesc* de
 // score_fused_capacity() (the waves the device holds at once: the kernel waits
 // inside a launch for a unit's items).  rowsum is a workspace of 32 doubles and
 // counters of 2 uint32 per `pos`, all zero on entry and left zero; q_rows DEVICE
-// int32[32]; *fault (host-visible) is set if a wait gave up after spin_limit polls.
+// int32[32]; fault (host-visible int[2]): [0] is set if a wait gave up after
+// spin_limit polls, [1] if a logit exceeded the range of the parked format.
 struct alignas(16) ScoreItem {
   int64_t in_off;    // first row of the unit's cached keys
   int32_t unit;      // u = b*H + h (rows of q/k_new start at u*N_k)

@@ -209,6 +209,7 @@ template <int N> __device__ __forceinline__ void score_wait_vm() {
 // importance are formed from the same parked value.  |t| is clamped to 511
 // (354 nats), far outside anything a float32 importance can resolve.
 constexpr double kFixOne = 4194304.0;  // 2^22
+constexpr int kFixLimit = 511 << 22;
 __device__ __forceinline__ int fix_from(double t_scaled) {  // t_scaled = t * 2^22
   t_scaled = fmin(fmax(t_scaled, -511.0 * kFixOne), 511.0 * kFixOne);
   return __double2int_rn(t_scaled);
@@ -249,8 +250,8 @@ __device__ __forceinline__ double half_sum_f64(double v) {
 // host never launches more waves than the device holds at once (occupancy x
 // compute units), so all of them run concurrently and each arrives without
 // depending on anyone else.  The wait is bounded all the same: a wave that runs
-// out of polls raises *fault (host-visible) and leaves without writing, and the
-// host refuses further work on the context.  The wave that is last to read a
+// out of polls raises fault[0] (host-visible) and leaves without writing, and the
+// host refuses further work on the context.  fault[1] reports clamped logits.  The wave that is last to read a
 // unit's sums zeroes sums and counters again for the next launch.
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void score_fused(
@@ -365,6 +366,22 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
     } else {
 #pragma unroll
       for (int r = 0; r < 16; ++r) tq[t][r] = 0;
+    }
+  }
+
+  // A logit that hit the clamp of the parked format makes the result differ from
+  // the definition: tell the host (second flag word; the launch still completes).
+  {
+    int hi = tq[0][0], lo = tq[0][0];
+#pragma unroll
+    for (int t = 0; t < kItemTiles; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        hi = max(hi, tq[t][r]);
+        lo = min(lo, tq[t][r]);
+      }
+    if (__any(hi >= kFixLimit || lo <= -kFixLimit)) {
+      if (lane == 0) __hip_atomic_store(fault + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
   }
 

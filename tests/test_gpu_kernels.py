@@ -245,6 +245,51 @@ def test_score_many_units_split_into_launch_groups_and_repeated_calls():
     hk.close()
 
 
+def test_score_extreme_logits_bf16():
+    """Logits of a few hundred nats: the row normalisers live in fp64, so peaked
+    rows must still follow the fp64 oracle over 100+ orders of magnitude (entries
+    that underflow float32 are compared absolutely; the relative bar is the one
+    the arithmetic supports at this logit magnitude, not the 1e-6 of ordinary data).  Beyond +-354 nats the parked logits are clamped: the
+    library must say so instead of returning a silently different answer."""
+    u = _u()
+    rng = np.random.default_rng(21)
+    H, B, d, Nk, dtype = 2, 1, 128, 40, "bf16"
+    hk = u.make_hack(heads=H, head_dim=d, dtype=dtype, max_units=2, max_cache_len=1024, max_queries=Nk)
+    rows = [(u.rand_values(rng, (n, d), dtype) * 4.0, u.rand_values(rng, (n, d), dtype)) for n in (700, 333)]
+    cin, _ = u.build_cache(rows, d, dtype)
+    q = wl.bf16_to_f32(wl.bf16_round(u.rand_values(rng, (B, H, Nk, d), dtype) * 4.0))
+    k_new = u.rand_values(rng, (B, H, Nk, d), dtype) * 4.0
+    obs = ho.observation_rows(Nk, 32)
+    qd, kd = torch.from_numpy(q).to(hk.torch_dtype).to(u.DEV), u.to_dev(k_new, dtype)
+    peak = max(float(np.abs(q[0, uu][obs].astype(np.float64) @ np.concatenate([rows[uu][0], k_new[0, uu]]).T.astype(np.float64)).max())
+               for uu in range(2))
+    scale = float(np.float32(300.0 / peak))                            # largest |logit| = 300 nats
+    imp = torch.full((2, 1024), -1.0, device=u.DEV)
+    hk.score(qd, cin, scale, imp, k_new=kd)
+    torch.cuda.synchronize()
+    hk.check()
+    got = imp.cpu().numpy().astype(np.float64)
+    for uu in range(2):
+        K_in = np.concatenate([rows[uu][0], k_new[0, uu]]).astype(np.float64)
+        want = ho.importance(q[0, uu][obs].astype(np.float64), K_in, scale)
+        err = np.abs(got[uu, :len(want)] - want)
+        # float32 slices of a dot product of magnitude 300 / scale carry ~2.5e-8 * |logit| of absolute
+        # error into the logit, i.e. that much relative error into exp(logit): 1e-5 at 300 nats
+        assert np.all(err <= 1e-5 * want + 1e-37), (uu, float((err / np.maximum(want, 1e-300)).max()))
+        assert abs(got[uu, :len(want)].sum() - len(obs)) < 1e-4 * len(obs)
+    # 500 nats: outside the supported range -> reported once, context stays usable
+    hk.score(qd, cin, float(np.float32(500.0 / peak)), imp, k_new=kd)
+    torch.cuda.synchronize()
+    with pytest.raises(HackError) as ei:
+        hk.check()
+    assert ei.value.status == -3
+    hk.check()
+    hk.score(qd, cin, scale, imp, k_new=kd)
+    torch.cuda.synchronize()
+    hk.check()
+    hk.close()
+
+
 def test_score_cache_only_custom_rows_and_inactive_units():
     u = _u()
     rng = np.random.default_rng(3)
