@@ -1,0 +1,221 @@
+"""Mutation checks of the pins: every planted mistake below (a dropped term, a
+wrong sign or index, a transposed operand, a wrong tie-break) is patched into the
+CPU oracle, and at least one pin of tests/test_oracle_pins.py has to fail.  A
+mistake that survives means the pins do not constrain that part of the oracle.
+Everything here runs on the CPU; nothing is planted in the GPU path."""
+import numpy as np
+import pytest
+
+from oracle import hack_oracle as ho
+from tests import test_oracle_pins as pins
+
+
+def _run_pins():
+    """Run every pin (parametrised ones with their parameters); return the names that failed."""
+    failed = []
+
+    def call(name, fn, *args):
+        try:
+            fn(*args)
+        except AssertionError:
+            failed.append(name)
+        except Exception as e:  # a mutant may also break shapes: that counts as caught
+            failed.append(f"{name} ({type(e).__name__})")
+
+    call("observation_rows", pins.test_observation_rows_stride_and_small_scales)
+    for p in [(3, 7, 4, 0.5), (5, 11, 6, 0.37), (1, 4, 3, 1.0)]:
+        call("importance_pure_python", pins.test_importance_matches_pure_python, *p)
+    call("importance_closed_forms", pins.test_importance_closed_forms)
+    call("importance_invariants", pins.test_importance_invariants_and_scale)
+    call("topk_hand", pins.test_topk_hand_computed)
+    call("structural_hand", pins.test_structural_hand_computed)
+    call("structural_small_budget", pins.test_structural_small_budget_reading)
+    call("all_equal", pins.test_all_equal_importance_closed_form)
+    call("float32_decision", pins.test_decision_is_taken_in_float32)
+    for seed in range(6):
+        call("select_brute_force", pins.test_select_matches_brute_force_and_invariants, seed)
+    call("compact", pins.test_compact_is_a_row_gather)
+    call("attention", pins.test_attention_matches_pure_python_and_properties)
+    call("full_budget_schedule", pins.test_full_budget_schedule_is_vanilla_cache_attention)
+    call("budget_equal", pins.test_budget_equal_to_cache_is_not_compressed_and_budget_100_equals_full)
+    call("compress_before_attention", pins.test_unit_step_compresses_before_attention)
+    call("schedule_invariants", pins.test_schedule_invariants_under_compression)
+    return failed
+
+
+def test_the_unmutated_oracle_passes_every_pin():
+    assert _run_pins() == []
+
+
+# ---- planted mistakes -------------------------------------------------------
+def _softmax_no_normaliser(S):
+    S = S - S.max(axis=1, keepdims=True)
+    return np.exp(S)
+
+
+def _softmax_over_queries(S):                     # normalises the wrong axis
+    S = S - S.max(axis=0, keepdims=True)
+    E = np.exp(S)
+    return E / E.sum(axis=0, keepdims=True)
+
+
+def _subset_attention_no_scale(Q_obs, K, scale):
+    return ho.softmax_rows(Q_obs @ K.T)
+
+
+def _subset_attention_negated(Q_obs, K, scale):
+    return ho.softmax_rows(-scale * (Q_obs @ K.T))
+
+
+def _importance_mean_instead_of_sum(Q_obs, K, scale):
+    return ho.subset_attention(Q_obs, K, scale).mean(axis=0)
+
+
+def _importance_max_instead_of_sum(Q_obs, K, scale):
+    return ho.subset_attention(Q_obs, K, scale).max(axis=0)
+
+
+def _observation_rows_first_rows(N_k, N_obs=32):  # first rows instead of a strided sample
+    return np.arange(min(N_obs, N_k), dtype=np.int64)
+
+
+def _observation_rows_ceil(N_k, N_obs=32):
+    n_obs = min(N_obs, N_k)
+    i = np.arange(n_obs, dtype=np.int64)
+    return np.minimum(-((-i * N_k) // n_obs) + (N_k > n_obs), N_k - 1)
+
+
+def _topk_smallest(values, k):
+    return _orig_topk(-values, k)
+
+
+def _topk_ties_to_higher_index(values, k):
+    k = int(k)
+    n = values.shape[0]
+    if k <= 0:
+        return np.zeros(0, np.int64)
+    if k >= n:
+        return np.arange(n, dtype=np.int64)
+    order = np.argsort(-values[::-1], kind="stable")
+    return np.sort((n - 1 - order)[:k]).astype(np.int64)
+
+
+def _topk_unsorted_output(values, k):
+    k = int(k)
+    n = values.shape[0]
+    if k <= 0:
+        return np.zeros(0, np.int64)
+    if k >= n:
+        return np.arange(n, dtype=np.int64)
+    return np.argsort(-values, kind="stable")[:k].astype(np.int64)
+
+
+def _topk_one_short(values, k):
+    return _orig_topk(values, max(int(k) - 1, 0))
+
+
+def _structural_no_init(imp, B_S, N_init, N_k):
+    return _orig_structural(imp, B_S, 0, N_k)
+
+
+def _structural_recent_off_by_one(imp, B_S, N_init, N_k):
+    return _orig_structural(imp, B_S, N_init, max(int(N_k) - 1, 0))
+
+
+def _structural_ranks_whole_cache(imp, B_S, N_init, N_k):   # forgets the protected windows
+    return ho.select_contextual(imp, B_S)
+
+
+def _structural_decides_in_float64(imp, B_S, N_init, N_k):
+    saved = ho.decision_values
+    ho.decision_values = lambda x: np.asarray(x, dtype=np.float64)
+    try:
+        return _orig_structural(imp, B_S, N_init, N_k)
+    finally:
+        ho.decision_values = saved
+
+
+def _contextual_decides_in_float64(imp, B_C):
+    return ho.topk_indices(np.asarray(imp, np.float64), min(int(B_C), imp.shape[0]))
+
+
+def _compact_swaps_k_and_v(K, V, I):
+    return V[I], K[I]
+
+
+def _compact_reversed(K, V, I):
+    return K[I[::-1]], V[I[::-1]]
+
+
+def _attention_transposed_scores(Q, K, V, scale):
+    S = scale * (Q @ K.T)
+    P = _softmax_over_queries(S)
+    return P @ V
+
+
+def _attention_no_scale(Q, K, V, scale):
+    return ho.softmax_rows(Q @ K.T) @ V
+
+
+def _attention_uses_keys_as_values(Q, K, V, scale):
+    return ho.softmax_rows(scale * (Q @ K.T)) @ K
+
+
+def _attention_causal(Q, K, V, scale):               # a mask inside the scale step
+    S = scale * (Q @ K.T)
+    n_q, n_k = S.shape
+    j = np.arange(n_k)[None, :]
+    i = np.arange(n_q)[:, None] + (n_k - n_q)
+    return ho.softmax_rows(np.where(j <= i, S, -1e30)) @ V
+
+
+_orig_topk = ho.topk_indices
+_orig_structural = ho.select_structural
+
+MUTANTS = [
+    ("softmax_rows", _softmax_no_normaliser),
+    ("softmax_rows", _softmax_over_queries),
+    ("subset_attention", _subset_attention_no_scale),
+    ("subset_attention", _subset_attention_negated),
+    ("importance", _importance_mean_instead_of_sum),
+    ("importance", _importance_max_instead_of_sum),
+    ("observation_rows", _observation_rows_first_rows),
+    ("observation_rows", _observation_rows_ceil),
+    ("topk_indices", _topk_smallest),
+    ("topk_indices", _topk_ties_to_higher_index),
+    ("topk_indices", _topk_unsorted_output),
+    ("topk_indices", _topk_one_short),
+    ("select_structural", _structural_no_init),
+    ("select_structural", _structural_recent_off_by_one),
+    ("select_structural", _structural_ranks_whole_cache),
+    ("select_structural", _structural_decides_in_float64),
+    ("select_contextual", _contextual_decides_in_float64),
+    ("compact", _compact_swaps_k_and_v),
+    ("compact", _compact_reversed),
+    ("attention", _attention_transposed_scores),
+    ("attention", _attention_no_scale),
+    ("attention", _attention_uses_keys_as_values),
+    ("attention", _attention_causal),
+]
+
+
+@pytest.mark.parametrize("target,mutant", MUTANTS, ids=[f"{t}:{m.__name__.lstrip('_')}" for t, m in MUTANTS])
+def test_planted_mistake_is_caught(monkeypatch, target, mutant):
+    monkeypatch.setattr(ho, target, mutant)
+    failed = _run_pins()
+    assert failed, f"no pin noticed {mutant.__name__} planted into oracle.{target}"
+
+
+def test_compress_after_attention_is_caught(monkeypatch):
+    """A schedule that attends over the uncompressed keys and compresses afterwards."""
+    orig = ho.unit_step
+
+    def late(Kc, Vc, Pc, Qk, Kk, Vk, pos0, head_type, budget, N_init, scale, *a, **kw):
+        out = dict(orig(Kc, Vc, Pc, Qk, Kk, Vk, pos0, head_type, budget, N_init, scale, *a, **kw))
+        out["O"] = ho.attention(Qk, np.concatenate([Kc, Kk]), np.concatenate([Vc, Vk]), scale)
+        return out
+
+    monkeypatch.setattr(ho, "unit_step", late)
+    failed = _run_pins()
+    assert any(name.startswith("compress_before_attention") or name.startswith("schedule_invariants")
+               for name in failed), failed

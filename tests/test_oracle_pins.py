@@ -173,6 +173,14 @@ def test_decision_is_taken_in_float32():
     assert list(ho.select_contextual(imp, 1)) == [0]
     imp = np.array([0.25, 0.25 + 1e-6, 0.1])      # distinct in float32
     assert list(ho.select_contextual(imp, 1)) == [1]
+    # the same rule inside the structural policy: middle rows 1..3, one of them kept
+    imp = np.array([9.0, 0.25, 0.25 + 1e-12, 0.1, 9.0])
+    assert list(ho.select_structural(imp, 3, 1, 1)) == [0, 1, 4]
+    imp = np.array([9.0, 0.25, 0.25 + 1e-6, 0.1, 9.0])
+    assert list(ho.select_structural(imp, 3, 1, 1)) == [0, 2, 4]
+    # and in the small-budget reading (ranking inside the recent rows)
+    imp = np.array([9.0, 0.1, 0.25, 0.25 + 1e-12])
+    assert list(ho.select_structural(imp, 2, 1, 3)) == [0, 2]
 
 
 @pytest.mark.parametrize("seed", range(6))
