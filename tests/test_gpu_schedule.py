@@ -184,3 +184,69 @@ def test_step_capacity_and_argument_errors():
     mc.reset()
     assert list(mc.view()[1]) == [0, 0]
     hk.close()
+
+
+def test_graph_replays_reproduce_the_eager_schedule():
+    """The whole schedule captured in a HIP graph (as bench.py launches it) is
+    replayed several times, with eager work and synchronisations in between;
+    every replay must reproduce the eager outputs, kept indices and final cache
+    bit for bit (the kernels' workspaces have to come back clean every time)."""
+    u = _u()
+    cfg = wl.get_config(1, batch=2)
+    layer = 0
+    hk = u.make_hack(cfg)
+    types = wl.head_types(cfg, layer)
+    cap = np.minimum(np.tile(wl.head_budgets(cfg, layer), cfg.batch), cfg.T_K)
+    mc = hk.managed_cache(cap)
+    data = wl.gen_layer(cfg, layer)
+    budgets = [wl.step_budgets(cfg, layer, k) for k in range(1, cfg.n_steps + 1)]
+    stride = (cfg.T_K + 63) // 64 * 64
+    q = [u.to_dev(data[k].q, cfg.dtype) for k in range(1, cfg.n_steps + 1)]
+    kn = [u.to_dev(data[k].k, cfg.dtype) for k in range(1, cfg.n_steps + 1)]
+    vn = [u.to_dev(data[k].v, cfg.dtype) for k in range(1, cfg.n_steps + 1)]
+    out = [torch.zeros_like(x) for x in q]
+    kept = [torch.full((cfg.n_units, stride), -1, dtype=torch.int32, device=u.DEV) for _ in q]
+
+    def run():
+        mc.reset()
+        for i in range(cfg.n_steps):
+            hk.step(mc, q[i], kn[i], vn[i], types, budgets[i], cfg.n_init, cfg.scale, out[i], kept_idx=kept[i])
+
+    def snapshot():
+        torch.cuda.synchronize()
+        off, ln = mc.view()
+        Kc, Vc = mc.k.clone(), mc.v.clone()
+        return ([o.clone() for o in out], [k.clone() for k in kept], off.copy(), ln.copy(), Kc, Vc)
+
+    run()
+    ref = snapshot()
+    st = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(st):
+        with torch.cuda.graph(g, stream=st):
+            run()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for o in out:
+            o.zero_()
+        for k in kept:
+            k.fill_(-1)
+        # unrelated eager work through the same context between replays
+        imp = torch.zeros((cfg.n_units, stride), device=u.DEV)
+        pre = mc.as_cache()
+        hk.score(q[-1], pre, cfg.scale, imp)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(st):
+            g.replay()
+        got = snapshot()
+        hk.check()
+        for a, b in zip(ref[0], got[0]):
+            assert torch.equal(a, b), rep
+        for a, b in zip(ref[1], got[1]):
+            assert torch.equal(a, b), rep
+        assert np.array_equal(ref[2], got[2]) and np.array_equal(ref[3], got[3])
+        for uu in range(cfg.n_units):
+            o, n = int(ref[2][uu]), int(ref[3][uu])
+            assert torch.equal(ref[4][o:o + n], got[4][o:o + n]) and torch.equal(ref[5][o:o + n], got[5][o:o + n])
+    mc.close()
+    hk.close()
