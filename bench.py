@@ -134,47 +134,54 @@ def breakdown(hk, ls, wl, torch, reps=5):
     return t
 
 
-def cpu_baseline(cfg, layer, wl, budget_s=15.0):
-    """The oracle as it stands, on the host cores, on a bounded sample of units."""
+def cpu_baseline(cfg, layer, wl, budget_s=12.0, max_layers=4):
+    """The oracle as it stands, on the host cores, on a bounded sample of the
+    workload: whole schedules of single units, alternating head classes, over
+    successive layers until about budget_s seconds of CPU work are spent."""
     from oracle import hack_oracle as ho
     try:
         from threadpoolctl import threadpool_info
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    types = wl.head_types(cfg, layer)
-    data = wl.gen_layer(cfg, layer)
-    steps = [(data[k].q, data[k].k, data[k].v) for k in range(1, cfg.n_steps + 1)]
-    budgets = [wl.step_budgets(cfg, layer, k) for k in range(1, cfg.n_steps + 1)]
-    ctx = [int(h) for h in np.where(types == 0)[0]]
-    st = [int(h) for h in np.where(types == 1)[0]]
-    if not ctx or not st:
-        ctx = st = list(range(cfg.heads))
-    sample, spent = [], 0.0
-    # alternate classes so the sample keeps the workload's contextual/structural mix in view
-    order = [u for pair in zip(st, ctx + st) for u in pair] + list(range(cfg.n_units))
-    seen = set()
-    t_per = {}
-    for u in order:
-        if u in seen:
-            continue
-        seen.add(u)
-        t0 = time.perf_counter()
-        ho.run_schedule(steps, types, budgets, cfg.n_init, cfg.scale, cfg.n_obs, units=[u], keep_outputs=False)
-        dt = time.perf_counter() - t0
-        t_per.setdefault(int(types[u % cfg.heads]), []).append(dt)
-        sample.append(u)
-        spent += dt
+    t_per, n_units, spent, layers_used = {}, 0, 0.0, 0
+    for lay in range(layer, layer + max_layers):
         if spent > budget_s:
             break
-    n_c = int((np.tile(types, cfg.batch) == 0).sum())
+        layers_used += 1
+        types = wl.head_types(cfg, lay)
+        data = wl.gen_layer(cfg, lay)
+        steps = [(data[k].q, data[k].k, data[k].v) for k in range(1, cfg.n_steps + 1)]
+        budgets = [wl.step_budgets(cfg, lay, k) for k in range(1, cfg.n_steps + 1)]
+        ctx = [int(h) for h in np.where(types == 0)[0]]
+        st = [int(h) for h in np.where(types == 1)[0]]
+        if not ctx or not st:
+            ctx = st = list(range(cfg.heads))
+        # alternate classes so a cut-off sample keeps the workload's contextual/structural mix in view
+        order = [u for pair in zip(st, ctx + st) for u in pair] + list(range(cfg.n_units))
+        seen = set()
+        for u in order:
+            if u in seen:
+                continue
+            seen.add(u)
+            t0 = time.perf_counter()
+            ho.run_schedule(steps, types, budgets, cfg.n_init, cfg.scale, cfg.n_obs, units=[u], keep_outputs=False)
+            dt = time.perf_counter() - t0
+            t_per.setdefault(int(types[u % cfg.heads]), []).append(dt)
+            n_units += 1
+            spent += dt
+            if spent > 2.5 * budget_s:
+                break
+    types0 = wl.head_types(cfg, layer)
+    n_c = int((np.tile(types0, cfg.batch) == 0).sum())
     n_s = cfg.n_units - n_c
     mean_c = float(np.mean(t_per.get(0, t_per.get(1))))
     mean_s = float(np.mean(t_per.get(1, t_per.get(0))))
     layer_s = n_c * mean_c + n_s * mean_s
     return dict(value=layer_s * 1e6, unit="us/layer", cores=int(cores), kind="oracle",
-                sample=f"{len(sample)} of {cfg.n_units} units of layer {layer}, whole schedule each, "
-                       f"{spent:.1f} s measured, scaled by class counts ({n_c} contextual, {n_s} structural)")
+                sample=f"{n_units} unit schedules from {layers_used} layer(s) starting at layer {layer}, "
+                       f"{spent:.1f} s measured; per-class means scaled to one layer "
+                       f"({n_c} contextual, {n_s} structural units)")
 
 
 def committed_traffic(cfg, kernel):
