@@ -59,6 +59,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
   __shared__ int wave_tot[kWaves];
   __shared__ uint32_t s_bin;
   __shared__ int s_want;
+  __shared__ int s_eq;    // candidates in the chosen bin (after the last pass: keys equal to the threshold)
 
   const UnitDesc d = descs[list[blockIdx.x]];
   const float* imp = importance + (int64_t)d.unit * imp_stride;
@@ -99,6 +100,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
           if (running < want && want <= running + c[e]) {
             s_bin = (uint32_t)(255 - 4 * tid - e);
             s_want = want - running;
+            s_eq = c[e];
           }
           running += c[e];
         }
@@ -117,13 +119,18 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
   const int per = (T + kThreads - 1) / kThreads;
   const int j0 = min(tid * per, T), j1 = min(j0 + per, T);
 
-  int n_eq = 0;
-  if (!take_all && !take_none) {
+  // The rank of a threshold-equal row among its equals (lowest index first) only
+  // matters if some of them are left out; usually the threshold value occurs
+  // once and is taken, and the first block scan can be skipped.
+  const bool all_equal_kept = take_all || take_none || (want >= s_eq);
+  int eq_rank = 0;
+  if (!all_equal_kept) {
+    int n_eq = 0;
     const int a = max(j0, d.sel_lo), b = min(j1, d.sel_hi);
     for (int j = a; j < b; ++j) n_eq += (keys[j - d.sel_lo] == tau);
+    int tot_eq;
+    eq_rank = block_exclusive_scan(n_eq, wave_tot, tot_eq);
   }
-  int tot_eq;
-  int eq_rank = block_exclusive_scan(n_eq, wave_tot, tot_eq);
 
   auto kept = [&](int j, int& eq_seen) -> bool {
     if (j < d.keep_a || j >= d.keep_b) return true;
@@ -132,7 +139,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     if (take_none) return false;
     const uint32_t k = keys[j - d.sel_lo];
     if (k > tau) return true;
-    if (k == tau) return (eq_seen++) < want;
+    if (k == tau) return all_equal_kept || (eq_seen++) < want;
     return false;
   };
 
