@@ -39,17 +39,24 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
     ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--full-budget", action="store_true",
+                    help="reference run: budgets = the whole cache, i.e. the same kernels with no compression "
+                         "(plain KV-cache attention over all previous scales)")
     return ap.parse_args()
 
 
 class LayerState:
     """Inputs of one layer resident on the device + its managed cache."""
 
-    def __init__(self, hk, cfg, layer, wl, torch):
+    def __init__(self, hk, cfg, layer, wl, torch, full_budget=False):
         self.cfg, self.layer = cfg, layer
         self.types = wl.head_types(cfg, layer)
         self.budgets = [wl.step_budgets(cfg, layer, k) for k in range(1, cfg.n_steps + 1)]
         cap = np.minimum(np.tile(wl.head_budgets(cfg, layer), cfg.batch), cfg.T_K)
+        if full_budget:
+            self.budgets = [np.full(cfg.n_units, wl.NO_COMPRESSION, np.int32) for _ in self.budgets]
+            cap = np.full(cfg.n_units, cfg.T_K, np.int64)
+        self.cap = cap
         self.mc = hk.managed_cache(cap, with_pos=True)
         dev = torch.device("cuda", 0)
         self.q, self.k, self.v, self.o = [], [], [], []
@@ -70,6 +77,18 @@ class LayerState:
         self.mc.reset()
         for i in range(c.n_steps):
             hk.step(self.mc, self.q[i], self.k[i], self.v[i], self.types, self.budgets[i], c.n_init, c.scale, self.o[i])
+
+
+def plan_of(cfg, budgets):
+    """Per step (L before, T_in, len_out) per unit for the budgets actually used."""
+    L = np.zeros(cfg.n_units, np.int64)
+    plan = []
+    for i in range(cfg.n_steps):
+        t_in = L + cfg.N[i]
+        len_out = np.minimum(budgets[i].astype(np.int64), t_in)
+        plan.append((L.copy(), t_in, len_out))
+        L = len_out
+    return plan
 
 
 def time_events(torch, fn, reps):
@@ -104,14 +123,14 @@ def breakdown(hk, ls, wl, torch, reps=5):
     stride = (c.T_K + 63) // 64 * 64
     imp = torch.zeros((c.n_units, stride), device=dev)
     kept = torch.zeros((c.n_units, stride), dtype=torch.int32, device=dev)
-    cap = np.minimum(np.tile(wl.head_budgets(c, ls.layer), c.batch), c.T_K)
+    cap = ls.cap
     off_s = np.concatenate([[0], np.cumsum((cap + 7) // 8 * 8)])[:-1].astype(np.int64)
     rows_s = int(((cap + 7) // 8 * 8).sum())
     ks = torch.empty((rows_s, c.head_dim), dtype=hk.torch_dtype, device=dev)
     vs = torch.empty_like(ks)
     t = dict(score=[], select=[], compact=[], attn=[])
     ls.mc.reset()
-    plan = wl.planned_lengths(c, ls.layer)
+    plan = plan_of(c, ls.budgets)
     for i in range(c.n_steps):
         L, t_in, len_out = plan[i]
         comp = (len_out < t_in)
@@ -221,7 +240,7 @@ def main():
         return
     cfg = wl.get_config(args.config, batch=args.batch)
     hk = Hack(cfg.heads, cfg.head_dim, cfg.dtype, cfg.n_units, cfg.T_K, max(cfg.N), cfg.n_obs)
-    layers = [LayerState(hk, cfg, l, wl, torch) for l in range(args.layers)]
+    layers = [LayerState(hk, cfg, l, wl, torch, args.full_budget) for l in range(args.layers)]
 
     # eager warm-up: uploads every launch table once
     for ls in layers:
@@ -258,7 +277,19 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
     work = wl.work_model(cfg, 0)
+    if args.full_budget:   # no compression: every step attends over the whole cache
+        for r in work:
+            r.update(attn_flop=r["full_attn_flop"], score_flop=0.0, score_bytes=0.0, select_bytes=0.0,
+                     compact_bytes=0.0, n_compress=0)
     tot = {k: sum(r[k] for r in work) for k in work[0] if k not in ("k", "N_k")}
+    # KV-cache bytes of one layer: what plain caching would hold, the largest logical cache the schedule
+    # passes through (right before a compression), what is retained at the end, and what is allocated
+    plan = plan_of(cfg, layers[0].budgets)
+    row_bytes = 2 * cfg.head_dim * cfg.elem_bytes
+    kv_bytes = {"uncompressed": int(cfg.T_K) * cfg.n_units * row_bytes,
+                "logical_peak": int(max(int(t_in.sum()) for _, t_in, _ in plan)) * row_bytes,
+                "final": int(plan[-1][2].sum()) * row_bytes,
+                "allocated": int(layers[0].mc.k.shape[0]) * row_bytes}
     result = {
         "metric": "full-schedule us/layer", "value": ms_per_step * 1e3, "unit": "us/layer",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -267,6 +298,8 @@ def main():
         "config": {"workload": cfg.name, "units": cfg.n_units, "heads": cfg.heads, "head_dim": cfg.head_dim,
                    "batch": cfg.batch, "scales": len(cfg.sides), "tokens": cfg.T_K, "launch": args.mode,
                    "layers_resident": args.layers},
+        "budgets": "full cache (no compression)" if args.full_budget else "workload default",
+        "kv_bytes_per_layer": kv_bytes,
         "attn_gflop_per_layer": tot["attn_flop"] / 1e9,
         "compress_mb_per_layer": (tot["score_bytes"] + tot["select_bytes"] + tot["compact_bytes"]) / 1e6,
     }
