@@ -15,7 +15,7 @@ Notation (paper, Preliminaries and Sec. 4):
   K, V  one head's cache (rows = tokens)       B_C, B_S  per-class budgets
   N_obs observation queries (32)               N_init tokens of the first two scales
 
-Readings taken where the paper is silent (each listed in the design doc):
+Readings taken where the paper is silent:
   * softmax scale is an explicit argument (the equations print none);
   * "uniformly sample" = the evenly strided rows floor(i*N_k/n_obs);
   * n_obs = min(N_obs, N_k);
@@ -28,7 +28,9 @@ Readings taken where the paper is silent (each listed in the design doc):
 
 Pinned by tests/test_oracle_pins.py (brute force in pure Python on tiny
 inputs, closed forms, invariants, the full-budget reduction to plain attention
-and the complexity closed form of the supplementary analysis).
+and the complexity closed form of the supplementary analysis); the pins
+themselves are checked by tests/test_oracle_mutations.py, which plants
+mistakes into this file's functions and requires a pin to fail.
 """
 from __future__ import annotations
 
@@ -107,7 +109,7 @@ def select_structural(imp: np.ndarray, B_S: int, N_init: int, N_k: int) -> np.nd
         mid = n0 + topk_indices(vals[n0:T - n_rec], M)
         rec = np.arange(T - n_rec, T, dtype=np.int64)
         return np.concatenate([init, mid, rec])
-    # Budget smaller than init + recent (reading of the design doc; parity unpinned):
+    # Budget smaller than init + recent (the paper is silent; this reading is unpinned):
     # the init rows first, then the best of the recent scale, nothing from the middle.
     n_keep0 = min(n0, B_S)
     init = np.arange(n_keep0, dtype=np.int64)
