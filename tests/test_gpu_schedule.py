@@ -102,6 +102,22 @@ def test_cfg2_full_size_sampled_units():
     assert stats["mismatch"] == 0 and stats["compress_events"] >= 4 + 3 * 3
 
 
+def test_cfg2_second_layer_and_cfg3_sampled_units():
+    """Another layer of the benchmark workload (other head mask, other data) and
+    the 32-head 1024^2 shape; full size on the device, a stated sample of units
+    through the oracle."""
+    cfg = wl.get_config(2)
+    types = wl.head_types(cfg, 1)
+    units = [int(np.where(types == 0)[0][-1]), int(np.where(types == 1)[0][-1]), cfg.heads + int(np.where(types == 0)[0][0])]
+    stats = run_free(cfg, 1, units)
+    assert stats["mismatch"] == 0 and stats["compress_events"] >= 4 + 3 + 4
+    cfg = wl.get_config(3)
+    types = wl.head_types(cfg, 0)
+    units = [int(np.where(types == 0)[0][0]), int(np.where(types == 1)[0][0]), cfg.n_units - 1]
+    stats = run_free(cfg, 0, units)
+    assert stats["mismatch"] == 0 and stats["compress_events"] >= 6
+
+
 def test_cfg4_ragged_budgets_small_batch():
     cfg = wl.get_config(4, keep=0.5, ctx_frac=0.25, batch=1)
     stats = run_free(cfg, 2, [0, 3, 5, 11], steps=11)
