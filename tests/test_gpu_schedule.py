@@ -21,11 +21,11 @@ def _tol(cfg):
     return 1e-4 if cfg.dtype == "f32" else 2e-2
 
 
-def run_free(cfg, layer, units, steps=None):
+def run_free(cfg, layer, units, steps=None, types=None):
     """hack_step over the schedule on all units; oracle on `units`.  Returns statistics."""
     u = _u()
     hk = u.make_hack(cfg)
-    types = wl.head_types(cfg, layer)
+    types = wl.head_types(cfg, layer) if types is None else np.asarray(types, np.uint8)
     cap = np.minimum(np.tile(wl.head_budgets(cfg, layer), cfg.batch), cfg.T_K)
     mc = hk.managed_cache(cap)
     n_steps = cfg.n_steps if steps is None else steps
@@ -116,6 +116,17 @@ def test_cfg2_second_layer_and_cfg3_sampled_units():
     units = [int(np.where(types == 0)[0][0]), int(np.where(types == 1)[0][0]), cfg.n_units - 1]
     stats = run_free(cfg, 0, units)
     assert stats["mismatch"] == 0 and stats["compress_events"] >= 6
+
+
+def test_swapped_policies_and_single_class_masks():
+    """The head-class mask is an argument: the paper's ablations (policies swapped
+    between the head groups, one policy for every head) are the same path with
+    another mask and must match the oracle just the same."""
+    cfg = wl.get_config(1, batch=1)
+    planted = wl.head_types(cfg, 0)
+    for types in (1 - planted, np.zeros_like(planted), np.ones_like(planted)):
+        stats = run_free(cfg, 0, list(range(0, cfg.n_units, 3)), types=types)
+        assert stats["mismatch"] == 0 and stats["compress_events"] > 0
 
 
 def test_cfg4_ragged_budgets_small_batch():
