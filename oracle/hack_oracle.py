@@ -24,7 +24,9 @@ Readings taken where the paper is silent:
   * a structural budget too small for init + recent keeps the init rows and
     the highest-scoring recent rows (parity unpinned: no passage fixes this);
   * the ranking is decided on importance rounded to float32, the precision in
-    which the device stores it, so that both sides decide on the same numbers.
+    which the device stores it, so that both sides decide on the same numbers;
+  * the attention variance of the head classification is the population
+    variance; alpha * L * H is rounded to the nearest integer.
 
 Pinned by tests/test_oracle_pins.py (brute force in pure Python on tiny
 inputs, closed forms, invariants, the full-budget reduction to plain attention
@@ -67,6 +69,33 @@ def subset_attention(Q_obs: np.ndarray, K: np.ndarray, scale: float) -> np.ndarr
 def importance(Q_obs: np.ndarray, K: np.ndarray, scale: float) -> np.ndarray:
     """Cumulative attention score of every key: sum_i A~[i, :] (f_C / f_S equations)."""
     return subset_attention(Q_obs, K, scale).sum(axis=0)
+
+
+# ---------------------------------------------------------------------------
+# Sec. 4.2, "Offline Head Classification via Attention Variance"
+# ---------------------------------------------------------------------------
+def head_variance(Q: np.ndarray, K: np.ndarray, scale: float) -> float:
+    """sigma = sum_j Var(A[:, j]) with A = Softmax(scale * Q K^T) the attention
+    matrix of the final step over the full (uncompressed) cache: the sum of the
+    column-wise variances across queries (variance equation of Sec. 4.2).
+    Reading: population variance (divide by the number of queries); the sample
+    variance differs by the constant factor N/(N-1), which no ranking sees."""
+    A = softmax_rows(scale * (Q @ K.T))
+    mean = A.sum(axis=0) / A.shape[0]
+    return float((((A - mean) ** 2).sum(axis=0) / A.shape[0]).sum())
+
+
+def classify_heads(sigma: np.ndarray, alpha: float) -> np.ndarray:
+    """Global ranking of all (layer, head) variance scores: the round(alpha * L * H)
+    heads of lowest variance are contextual (0), the others structural (1).
+    Ties go to the lower flat index.  sigma has shape [L, H] (or [H])."""
+    sigma = np.asarray(sigma, dtype=np.float64)
+    flat = sigma.reshape(-1)
+    n_ctx = int(round(float(alpha) * flat.shape[0]))
+    order = np.argsort(flat, kind="stable")
+    types = np.full(flat.shape[0], STRUCTURAL, dtype=np.uint8)
+    types[order[:n_ctx]] = CONTEXTUAL
+    return types.reshape(sigma.shape)
 
 
 # ---------------------------------------------------------------------------

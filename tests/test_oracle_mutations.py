@@ -40,6 +40,10 @@ def _run_pins():
     call("budget_equal", pins.test_budget_equal_to_cache_is_not_compressed_and_budget_100_equals_full)
     call("compress_before_attention", pins.test_unit_step_compresses_before_attention)
     call("schedule_invariants", pins.test_schedule_invariants_under_compression)
+    for prm in [(4, 9, 5, 0.6), (7, 3, 4, 1.3), (2, 6, 3, 0.25)]:
+        call("head_variance_pure_python", pins.test_head_variance_matches_pure_python, *prm)
+    call("head_variance_closed_forms", pins.test_head_variance_closed_forms_and_invariants)
+    call("classify_heads", pins.test_classify_heads_hand_computed_and_planted_mask)
     return failed
 
 
@@ -169,7 +173,38 @@ def _attention_causal(Q, K, V, scale):               # a mask inside the scale s
     return ho.softmax_rows(np.where(j <= i, S, -1e30)) @ V
 
 
+def _variance_sample_instead_of_population(Q, K, scale):
+    A = ho.softmax_rows(scale * (Q @ K.T))
+    return float(A.var(axis=0, ddof=1).sum())
+
+
+def _variance_across_keys(Q, K, scale):              # row-wise instead of column-wise
+    A = ho.softmax_rows(scale * (Q @ K.T))
+    return float(A.var(axis=1).sum())
+
+
+def _variance_of_logits(Q, K, scale):                # forgets the softmax
+    return float((scale * (Q @ K.T)).var(axis=0).sum())
+
+
+def _variance_mean_over_columns(Q, K, scale):
+    A = ho.softmax_rows(scale * (Q @ K.T))
+    return float(A.var(axis=0).mean())
+
+
+def _classify_high_variance_is_contextual(sigma, alpha):
+    return _orig_classify(-np.asarray(sigma, np.float64), alpha)
+
+
+def _classify_per_layer_ranking(sigma, alpha):       # ranks inside each layer instead of globally
+    sigma = np.asarray(sigma, np.float64)
+    if sigma.ndim < 2:
+        return _orig_classify(sigma, alpha)
+    return np.stack([_orig_classify(row, alpha) for row in sigma])
+
+
 _orig_topk = ho.topk_indices
+_orig_classify = ho.classify_heads
 _orig_structural = ho.select_structural
 
 MUTANTS = [
@@ -196,6 +231,12 @@ MUTANTS = [
     ("attention", _attention_no_scale),
     ("attention", _attention_uses_keys_as_values),
     ("attention", _attention_causal),
+    ("head_variance", _variance_sample_instead_of_population),
+    ("head_variance", _variance_across_keys),
+    ("head_variance", _variance_of_logits),
+    ("head_variance", _variance_mean_over_columns),
+    ("classify_heads", _classify_high_variance_is_contextual),
+    ("classify_heads", _classify_per_layer_ranking),
 ]
 
 

@@ -344,3 +344,71 @@ def test_complexity_closed_form_from_the_paper():
         assert ho.attention_cost_budgeted(N, 10 ** 9) == val
     # subset-attention overhead: N_obs * sum_{k>=k_s} (B + N_k)
     assert ho.subset_attention_cost([1, 4, 16, 64], B=10, k_s=3, N_obs=32) == 32 * ((10 + 16) + (10 + 64))
+
+
+# ---------------------------------------------------------------------------
+# offline head classification (attention variance)
+# ---------------------------------------------------------------------------
+def bf_head_variance(Q, K, scale):
+    rows = [bf_softmax_row([scale * bf_dot(q, k) for k in K]) for q in Q]
+    n = len(rows)
+    total = 0.0
+    for j in range(len(K)):
+        col = [r[j] for r in rows]
+        mean = math.fsum(col) / n
+        total += math.fsum((x - mean) ** 2 for x in col) / n
+    return total
+
+
+@pytest.mark.parametrize("n_q,T,d,scale", [(4, 9, 5, 0.6), (7, 3, 4, 1.3), (2, 6, 3, 0.25)])
+def test_head_variance_matches_pure_python(n_q, T, d, scale):
+    rng = np.random.default_rng(7 * n_q + T)
+    Q, K = rng.standard_normal((n_q, d)), rng.standard_normal((T, d))
+    assert abs(ho.head_variance(Q, K, scale) - bf_head_variance(Q.tolist(), K.tolist(), scale)) < 1e-13
+
+
+def test_head_variance_closed_forms_and_invariants():
+    rng = np.random.default_rng(5)
+    K = rng.standard_normal((11, 6))
+    # every query sees the same distribution -> no variance across queries
+    q = rng.standard_normal(6)
+    assert ho.head_variance(np.tile(q, (5, 1)), K, 0.7) < 1e-30
+    assert ho.head_variance(np.zeros((5, 6)), K, 0.7) < 1e-30
+    # two queries with rows a and b: population variance of {a_j, b_j} is ((a_j - b_j) / 2)^2
+    Q = rng.standard_normal((2, 6))
+    a, b = (np.array(bf_softmax_row([0.5 * bf_dot(qq, k) for k in K.tolist()])) for qq in Q.tolist())
+    assert abs(ho.head_variance(Q, K, 0.5) - float(np.sum((a - b) ** 2) / 4.0)) < 1e-15
+    # every query attends to its own key only: each of N columns holds one 1 and N-1 zeros,
+    # variance (1/N)(1 - 1/N) each, the other columns are 0: sigma = 1 - 1/N
+    N, T = 4, 7
+    Kk = np.eye(T, 8) * 10.0
+    assert abs(ho.head_variance(Kk[:N] * 10.0, Kk, 1.0) - (1.0 - 1.0 / N)) < 1e-12
+    # order of queries and of keys does not matter; bounds 0 <= sigma <= 1 - 1/N
+    Q = rng.standard_normal((6, 6))
+    s0 = ho.head_variance(Q, K, 0.9)
+    assert abs(ho.head_variance(Q[rng.permutation(6)], K, 0.9) - s0) < 1e-15
+    assert abs(ho.head_variance(Q, K[rng.permutation(11)], 0.9) - s0) < 1e-15
+    assert 0.0 <= s0 <= 1.0 - 1.0 / 6
+    # sum of squares identity: sigma = (1/N) sum_ij A_ij^2 - sum_j mean_j^2
+    A = np.array([bf_softmax_row([0.9 * bf_dot(qq, k) for k in K.tolist()]) for qq in Q.tolist()])
+    assert abs(s0 - (np.sum(A * A) / 6 - np.sum(A.mean(axis=0) ** 2))) < 1e-15
+
+
+def test_classify_heads_hand_computed_and_planted_mask():
+    sig = np.array([[0.5, 0.01, 0.3], [0.02, 0.7, 0.01]])
+    assert ho.classify_heads(sig, 0.5).tolist() == [[1, 0, 1], [0, 1, 0]]     # three lowest: 0.01, 0.01, 0.02
+    assert ho.classify_heads(sig, 1 / 3).tolist() == [[1, 0, 1], [1, 1, 0]]   # the tie 0.01/0.01 fills both places
+    assert ho.classify_heads(sig, 1 / 6).tolist() == [[1, 0, 1], [1, 1, 1]]   # tie: lower flat index first
+    assert ho.classify_heads(sig, 0.0).sum() == 6 and ho.classify_heads(sig, 1.0).sum() == 0
+    # the synthetic workload plants sinks (contextual) and a positional code (structural):
+    # the variance ranking has to recover the planted mask
+    from paper_2504_09261_amd import workload as wl
+    cfg = wl.get_config(0)
+    types = wl.head_types(cfg, 0)
+    data = wl.gen_layer(cfg, 0)
+    K = np.concatenate([data[k].k for k in range(1, cfg.n_steps + 1)], axis=2)
+    Q = data[cfg.n_steps].q
+    sig = np.array([ho.head_variance(Q[0, h].astype(np.float64), K[0, h].astype(np.float64), cfg.scale)
+                    for h in range(cfg.heads)])
+    assert np.array_equal(ho.classify_heads(sig, float((types == 0).mean())), types)
+    assert sig[types == 0].max() * 20 < sig[types == 1].min()                 # a clear boundary, as the paper describes
