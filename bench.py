@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
     ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--head-variance", action="store_true",
+                    help="also time the offline head-classification kernels (attention variance of every unit at the "
+                         "final step over the full cache) and report them in a head_variance object")
     ap.add_argument("--full-budget", action="store_true",
                     help="reference run: budgets = the whole cache, i.e. the same kernels with no compression "
                          "(plain KV-cache attention over all previous scales)")
@@ -203,6 +206,26 @@ def cpu_baseline(cfg, layer, wl, budget_s=12.0, max_layers=4):
                        f"({n_c} contextual, {n_s} structural units)")
 
 
+def head_variance_leg(hk, ls, torch, reps=5):
+    """Times hack_head_variance on the final step of the layer: all N_K queries against the full cache."""
+    from paper_2504_09261_amd.binding import Cache
+    c = ls.cfg
+    stride = (c.T_K + 7) // 8 * 8
+    k_all = torch.cat(ls.k, dim=2).reshape(c.n_units, c.T_K, c.head_dim)
+    kc = torch.zeros((c.n_units, stride, c.head_dim), dtype=k_all.dtype, device=k_all.device)
+    kc[:, :c.T_K] = k_all
+    kc = kc.reshape(c.n_units * stride, c.head_dim)
+    cache = Cache(kc, kc, np.arange(c.n_units, dtype=np.int64) * stride, np.full(c.n_units, c.T_K, np.int32))
+    sigma = torch.zeros(c.n_units, dtype=torch.float64, device=k_all.device)
+    q = ls.q[-1]
+    ms = time_events(torch, lambda: hk.head_variance(q, cache, c.scale, sigma), reps)
+    flop = 2 * 2.0 * c.N[-1] * c.T_K * c.head_dim * c.n_units          # two passes of Q K^T
+    return {"us": ms * 1e3, "gflop": flop / 1e9, "TFLOPs": flop / (ms * 1e-3) / 1e12,
+            "frac_mfma": flop / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+            "sigma_contextual_mean": float(sigma.cpu().numpy().reshape(c.batch, c.heads)[:, ls.types == 0].mean()),
+            "sigma_structural_mean": float(sigma.cpu().numpy().reshape(c.batch, c.heads)[:, ls.types == 1].mean())}
+
+
 def committed_traffic(cfg, kernel):
     """HBM bytes per launch of `kernel` on this workload from the committed
     counter summary (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, calibrated on
@@ -334,6 +357,9 @@ def main():
                                           "frac_hbm": ssc_b / 1e9 / (ssc_ms * 1e-3) / HBM_PEAK_GBPS if ssc_ms else None}
         stages["attn"] = {"us_per_layer": attn_ms * 1e3, "per_step_us": [round(x * 1e3, 1) for x in bd["attn"]]}
         result["stages"] = stages
+
+    if args.head_variance and cfg.dtype == "bf16":
+        result["head_variance"] = head_variance_leg(hk, layers[0], torch)
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, 0, wl)

@@ -173,6 +173,26 @@ hack_status hack_attn(hack_ctx* ctx, int32_t B, int32_t N_k, const void* q,
                       const hack_cache* kv, float scale, void* out,
                       hack_stream stream);
 
+/* ---- offline head classification: attention variance --------------------
+ * Sec. 4.2, "Offline Head Classification via Attention Variance": for every
+ * unit, A = Softmax(scale * Q K^T) over ALL keys of kv (the uncompressed cache
+ * of the final step) and all N_k queries, and
+ *   sigma[u] = sum_j Var_i(A[i, j])     (population variance across queries).
+ * The caller averages sigma over a validation set, ranks all (layer, head)
+ * pairs and calls the lowest alpha * L * H of them contextual; that ranking is
+ * host arithmetic on L * H numbers and is not part of this library.
+ *   q      DEVICE [B, H, N_k, d]
+ *   kv     the cache to attend over (kv->v may be NULL: values are not used)
+ *   sigma  DEVICE double [B*H], overwritten
+ * bf16 contexts only (HACK_EUNSUPPORTED otherwise).  Accuracy: probabilities
+ * are formed in float32 from chained MFMA scores (relative error ~1e-5 at most),
+ * the moments are accumulated in fp64.
+ * Errors: HACK_EINVAL (NULL/misaligned pointers, empty unit, bad scale),
+ * HACK_ECAPACITY (B*H or N_k above the context's limits). */
+hack_status hack_head_variance(hack_ctx* ctx, int32_t B, int32_t N_k, const void* q,
+                               const hack_cache* kv, float scale, double* sigma,
+                               hack_stream stream);
+
 /* ---- a5: the whole step on a library-managed cache -----------------------
  * The managed cache gives every unit two slabs of cap[u] rows inside memory
  * the caller provides (compaction writes from one slab to the other; a unit

@@ -22,7 +22,7 @@ EXPORTS = [
     "hack_create", "hack_destroy", "hack_strerror", "hack_last_error", "hack_check",
     "hack_score", "hack_select", "hack_compact", "hack_attn",
     "hack_kvcache_rows_required", "hack_kvcache_create", "hack_kvcache_destroy",
-    "hack_kvcache_reset", "hack_kvcache_view", "hack_step",
+    "hack_kvcache_reset", "hack_kvcache_view", "hack_step", "hack_head_variance",
 ]
 
 
@@ -73,6 +73,7 @@ def load_library() -> C.CDLL:
     lib.hack_select.argtypes = [vp, i32, vp, i64, pi32, pu8, pi32, i32, i32, vp, i64, pi32, vp]
     lib.hack_compact.argtypes = [vp, i32, i32, pcache, vp, vp, i32, vp, i64, pcache, vp]
     lib.hack_attn.argtypes = [vp, i32, i32, vp, pcache, f32, vp, vp]
+    lib.hack_head_variance.argtypes = [vp, i32, i32, vp, pcache, f32, vp, vp]
     lib.hack_kvcache_rows_required.argtypes = [i32, pi32, pi64]
     lib.hack_kvcache_create.argtypes = [vp, i32, pi32, vp, vp, vp, i64, C.POINTER(vp)]
     lib.hack_kvcache_destroy.argtypes = [vp]
@@ -246,6 +247,13 @@ class Hack:
         B, H, Nk, d = q.shape
         cs = cache.struct()
         self._check(self.lib.hack_attn(self.ctx, B, Nk, _dev(q), C.byref(cs), scale, _dev(out), _stream()))
+
+    # ---- offline head classification ----
+    def head_variance(self, q, cache: Cache, scale: float, sigma):
+        """sigma (device float64 [B*H]) <- sum of column variances of Softmax(scale q k^T) per unit."""
+        B, H, Nk, d = q.shape
+        cs = cache.struct()
+        self._check(self.lib.hack_head_variance(self.ctx, B, Nk, _dev(q), C.byref(cs), scale, _dev(sigma), _stream()))
 
     # ---- a5 ----
     def managed_cache(self, cap, with_pos: bool = True) -> ManagedCache:

@@ -44,6 +44,7 @@ struct hack_ctx {
   double* stats = nullptr;       // fp32 path: [max_units, max_chunks, 32, 2] softmax partials
   double* rowstat = nullptr;     // bf16 path: [max_units, 32] softmax normalisers, zero between launches
   unsigned* counters = nullptr;  // bf16 path: [max_units, 2] arrival / reader counters, zero between launches
+  float* hv_stats = nullptr;     // head variance: [max_units, max_queries, 2] softmax statistics of every query
   int* fault = nullptr;          // pinned, device-visible int[2]: [0] a score wave's bounded wait gave up (fatal),
                                  // [1] a logit exceeded the range the bf16 score kernel supports
   int score_capacity = 0;        // bf16 path: score items one launch may hold (resident waves)
@@ -328,6 +329,8 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->rowstat, (size_t)cfg->max_units * kMaxObs * 2 * sizeof(double));
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, (size_t)cfg->max_units * 2 * sizeof(unsigned));
   if (e == hipSuccess) e = hipMemset(ctx->counters, 0, (size_t)cfg->max_units * 2 * sizeof(unsigned));
+  if (e == hipSuccess && cfg->dtype == HACK_BF16)
+    e = hipMalloc((void**)&ctx->hv_stats, (size_t)cfg->max_units * cfg->max_queries * 2 * sizeof(float));
   if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->fault, 2 * sizeof(int), hipHostMallocDefault);
   if (e == hipSuccess) ctx->fault[0] = ctx->fault[1] = 0;
   if (e == hipSuccess) e = hipMemset(ctx->rowstat, 0, (size_t)cfg->max_units * kMaxObs * 2 * sizeof(double));
@@ -357,6 +360,7 @@ extern "C" void hack_destroy(hack_ctx* ctx) {
   if (ctx->rowstat) (void)hipFree(ctx->rowstat);
   if (ctx->counters) (void)hipFree(ctx->counters);
   if (ctx->fault) (void)hipHostFree(ctx->fault);
+  if (ctx->hv_stats) (void)hipFree(ctx->hv_stats);
   if (ctx->arena_dev) (void)hipFree(ctx->arena_dev);
   if (ctx->arena_host) (void)hipHostFree(ctx->arena_host);
   delete ctx;
@@ -548,6 +552,39 @@ extern "C" hack_status hack_attn(hack_ctx* ctx, int32_t B, int32_t N_k, const vo
   if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
   launch_attn(s, ctx->cfg.dtype, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), (const AttnItem*)(dev + o_items),
               (int)items.size(), tile, q, kv->k, kv->v, N_k, scale, out);
+  HIP_TRY(ctx, hipGetLastError());
+  return HACK_OK;
+}
+
+// ---------------------------------------------------------------------------
+// offline head classification: attention variance
+// ---------------------------------------------------------------------------
+extern "C" hack_status hack_head_variance(hack_ctx* ctx, int32_t B, int32_t N_k, const void* q, const hack_cache* kv,
+                                          float scale, double* sigma, hack_stream stream) {
+  hack_status st = check_common(ctx, B, N_k, true);
+  if (st != HACK_OK) return st;
+  if (ctx->cfg.dtype != HACK_BF16) return fail(ctx, HACK_EUNSUPPORTED, "head variance is implemented for bf16 contexts");
+  const int U = B * ctx->cfg.heads;
+  if (!q || !sigma) return fail(ctx, HACK_EINVAL, "q and sigma must not be NULL");
+  if (!aligned16(q) || ((uintptr_t)sigma & 7)) return fail(ctx, HACK_EINVAL, "q must be 16-byte and sigma 8-byte aligned");
+  if (!scale_ok(scale)) return fail(ctx, HACK_EINVAL, "scale must be finite and > 0");
+  if ((st = check_cache(ctx, kv, U, "kv", false)) != HACK_OK) return st;
+  std::vector<UnitDesc> descs(U);
+  int max_len = 0;
+  for (int u = 0; u < U; ++u) {
+    if (kv->len[u] < 1) return fail(ctx, HACK_EINVAL, "unit %d has an empty cache", u);
+    UnitDesc d{};
+    d.in_off = kv->off[u]; d.out_off = kv->off[u]; d.len_in = kv->len[u]; d.n_out = kv->len[u]; d.unit = u;
+    descs[u] = d;
+    max_len = std::max(max_len, (int)kv->len[u]);
+  }
+  Table t;
+  const size_t o_desc = t.add(descs.data(), descs.size());
+  const uint8_t* dev;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
+  launch_head_variance(s, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), U, max_len, q, kv->k, N_k, scale,
+                       ctx->hv_stats, sigma);
   HIP_TRY(ctx, hipGetLastError());
   return HACK_OK;
 }

@@ -96,6 +96,11 @@ size_t select_lds_bytes(int max_t_in);
 void launch_attn(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, const AttnItem* items,
                  int n_items, int q_tile_rows, const void* q, const void* k_cache,
                  const void* v_cache, int N_k, float scale, void* out);
+// Attention variance of the listed units (bf16): sigma[desc.unit] = sum over the
+// unit's n_out keys of the population variance, across its N_k queries, of the
+// softmax probabilities.  stats: workspace of 2 floats per (unit, query).
+void launch_head_variance(hipStream_t s, int head_dim, const UnitDesc* descs, int n_desc, int max_len, const void* q,
+                          const void* k_cache, int N_k, float scale, float* stats, double* sigma);
 // Query rows per attention work item for this dtype/head_dim and launch size.
 int attn_q_tile_rows(int dtype, int head_dim, int n_units, int N_k);
 
