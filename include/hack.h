@@ -172,6 +172,18 @@ hack_status hack_compact(hack_ctx* ctx, int32_t B, int32_t N_k,
 hack_status hack_attn(hack_ctx* ctx, int32_t B, int32_t N_k, const void* q,
                       const hack_cache* kv, float scale, void* out,
                       hack_stream stream);
+/* Which kernel hack_attn / hack_step use for the attention of a launch with B
+ * batch elements and N_k queries per unit (same attention equation, same
+ * tolerances; reported so that measurements can be attributed to a kernel):
+ *   0  work items of 128 queries that share every K/V block (large steps; fp32
+ *      contexts always),
+ *   1  work items of 32 queries whose four waves split the keys and merge their
+ *      partial softmax results at the end (bf16, early scale steps: few
+ *      queries); in hack_step this kernel also performs the append when no unit
+ *      of the step compresses.
+ * The choice depends only on B * H, N_k and the context's head_dim.
+ * Returns a negative hack_status for a NULL context or B, N_k < 1. */
+int32_t hack_attn_variant(const hack_ctx* ctx, int32_t B, int32_t N_k);
 
 /* ---- offline head classification: attention variance --------------------
  * Sec. 4.2, "Offline Head Classification via Attention Variance": for every

@@ -20,7 +20,7 @@ CONTEXTUAL, STRUCTURAL = 0, 1
 
 EXPORTS = [
     "hack_create", "hack_destroy", "hack_strerror", "hack_last_error", "hack_check",
-    "hack_score", "hack_select", "hack_compact", "hack_attn",
+    "hack_score", "hack_select", "hack_compact", "hack_attn", "hack_attn_variant",
     "hack_kvcache_rows_required", "hack_kvcache_create", "hack_kvcache_destroy",
     "hack_kvcache_reset", "hack_kvcache_view", "hack_step", "hack_head_variance",
 ]
@@ -73,6 +73,8 @@ def load_library() -> C.CDLL:
     lib.hack_select.argtypes = [vp, i32, vp, i64, pi32, pu8, pi32, i32, i32, vp, i64, pi32, vp]
     lib.hack_compact.argtypes = [vp, i32, i32, pcache, vp, vp, i32, vp, i64, pcache, vp]
     lib.hack_attn.argtypes = [vp, i32, i32, vp, pcache, f32, vp, vp]
+    lib.hack_attn_variant.argtypes = [vp, i32, i32]
+    lib.hack_attn_variant.restype = i32
     lib.hack_head_variance.argtypes = [vp, i32, i32, vp, pcache, f32, vp, vp]
     lib.hack_kvcache_rows_required.argtypes = [i32, pi32, pi64]
     lib.hack_kvcache_create.argtypes = [vp, i32, pi32, vp, vp, vp, i64, C.POINTER(vp)]
@@ -247,6 +249,13 @@ class Hack:
         B, H, Nk, d = q.shape
         cs = cache.struct()
         self._check(self.lib.hack_attn(self.ctx, B, Nk, _dev(q), C.byref(cs), scale, _dev(out), _stream()))
+
+    def attn_variant(self, B: int, N_k: int) -> int:
+        """0: 128-query work items; 1: 32-query work items with the keys split over the waves."""
+        v = int(self.lib.hack_attn_variant(self.ctx, B, N_k))
+        if v < 0:
+            self._check(v)
+        return v
 
     # ---- offline head classification ----
     def head_variance(self, q, cache: Cache, scale: float, sigma):

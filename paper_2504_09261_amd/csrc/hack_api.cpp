@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -48,6 +49,7 @@ struct hack_ctx {
   int* fault = nullptr;          // pinned, device-visible int[2]: [0] a score wave's bounded wait gave up (fatal),
                                  // [1] a logit exceeded the range the bf16 score kernel supports
   int score_capacity = 0;        // bf16 path: score items one launch may hold (resident waves)
+  int split_max_items = 0;       // launches with at most this many 32-query attention items use the key-split kernel
   int64_t ws_stride = 0;
   int max_chunks = 0;
   // launch-table cache
@@ -241,6 +243,21 @@ void build_attn_items(const std::vector<UnitDesc>& descs, int N_k, int tile_rows
     for (size_t i = 0; i < per[x].size(); ++i) (*items)[i * X + x] = per[x][i];
 }
 
+// Steps with few queries (the early scales) go to the key-split kernel (bf16
+// only): its 32-query work items fill the chip where 128-query tiles would not,
+// and a step that does not compress then needs no separate append launch.  It is
+// used while all of its work items are resident at once or nearly so; beyond
+// that the 128-query kernel, which shares every K/V block among four times as
+// many queries, is faster.  Measured cross-overs on MI355X: head_dim 128 between
+// 416 and 576 items (16 heads, batch 2); head_dim 64 between 1920 and 3840 items
+// (30 heads, batch 32).
+int split_max_items_default(int head_dim) { return head_dim == 64 ? 2048 : 512; }
+bool use_split_attention(const hack_ctx* ctx, int n_units, int N_k) {
+  if (ctx->cfg.dtype != HACK_BF16) return false;
+  const int tile = attn_split_q_tile_rows();
+  return (int64_t)n_units * ((N_k + tile - 1) / tile) <= ctx->split_max_items;
+}
+
 // One score work item per chunk of every listed unit, longest units first so the
 // tail of a launch is made of short units.  All items of a unit go into the same
 // launch group and no group exceeds `capacity` items; group_begin gets the first
@@ -321,6 +338,8 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   ctx->elem_bytes = cfg->dtype == HACK_F32 ? 4 : 2;
   ctx->ws_stride = round_up(cfg->max_cache_len, 64);
   ctx->max_chunks = (cfg->max_cache_len + kScoreChunk - 1) / kScoreChunk;
+  ctx->split_max_items = split_max_items_default(cfg->head_dim);
+  if (const char* v = std::getenv("HACK_ATTN_SPLIT_ITEMS")) ctx->split_max_items = std::atoi(v);   // tuning / test override
   hipError_t e = hipSetDevice(cfg->device);
   const size_t n_ws = (size_t)cfg->max_units * ctx->ws_stride;
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->importance, n_ws * sizeof(float));
@@ -541,7 +560,8 @@ extern "C" hack_status hack_attn(hack_ctx* ctx, int32_t B, int32_t N_k, const vo
     d.in_off = kv->off[u]; d.out_off = kv->off[u]; d.len_in = kv->len[u]; d.n_out = kv->len[u]; d.unit = u;
     descs[u] = d;
   }
-  const int tile = attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim, U, N_k);
+  const bool split = use_split_attention(ctx, U, N_k);
+  const int tile = split ? attn_split_q_tile_rows() : attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim, U, N_k);
   std::vector<AttnItem> items;
   build_attn_items(descs, N_k, tile, &items);
   Table t;
@@ -550,10 +570,20 @@ extern "C" hack_status hack_attn(hack_ctx* ctx, int32_t B, int32_t N_k, const vo
   const uint8_t* dev;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
-  launch_attn(s, ctx->cfg.dtype, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), (const AttnItem*)(dev + o_items),
-              (int)items.size(), tile, q, kv->k, kv->v, N_k, scale, out);
+  if (split)
+    launch_attn_split(s, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), (const AttnItem*)(dev + o_items),
+                      (int)items.size(), q, kv->k, kv->v, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, N_k, scale,
+                      out);
+  else
+    launch_attn(s, ctx->cfg.dtype, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), (const AttnItem*)(dev + o_items),
+                (int)items.size(), tile, q, kv->k, kv->v, N_k, scale, out);
   HIP_TRY(ctx, hipGetLastError());
   return HACK_OK;
+}
+
+extern "C" int32_t hack_attn_variant(const hack_ctx* ctx, int32_t B, int32_t N_k) {
+  if (!ctx || B < 1 || N_k < 1) return (int32_t)HACK_EINVAL;
+  return use_split_attention(ctx, B * ctx->cfg.heads, N_k) ? 1 : 0;
 }
 
 // ---------------------------------------------------------------------------
@@ -694,7 +724,9 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
   const int n_obs = std::min(ctx->cfg.n_obs, N_k);
   int32_t rows[kMaxObs];
   fill_q_rows(nullptr, n_obs, N_k, rows);
-  const int tile = attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim, U, N_k);
+  const bool split = use_split_attention(ctx, U, N_k);
+  const bool fuse_append = split && comp.empty();   // no unit compresses: the attention launch appends as well
+  const int tile = split ? attn_split_q_tile_rows() : attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim, U, N_k);
   std::vector<AttnItem> items;
   build_attn_items(descs, N_k, tile, &items);
 
@@ -721,10 +753,16 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
     launch_select(s, ddev, (const int32_t*)(dev + o_comp), (int)comp.size(), max_t, ctx->importance, ctx->ws_stride, kept,
                   kstride);
   }
-  launch_move(s, ctx->elem_bytes, ctx->cfg.head_dim, ddev, U, max_rows, cp, cp, k_new, v_new, N_k,
-              (int32_t)cache->tokens_seen, kept, kstride);
-  launch_attn(s, ctx->cfg.dtype, ctx->cfg.head_dim, ddev, (const AttnItem*)(dev + o_items), (int)items.size(), tile, q,
-              cache->k, cache->v, N_k, scale, out);
+  if (!fuse_append)
+    launch_move(s, ctx->elem_bytes, ctx->cfg.head_dim, ddev, U, max_rows, cp, cp, k_new, v_new, N_k,
+                (int32_t)cache->tokens_seen, kept, kstride);
+  if (split)
+    launch_attn_split(s, ctx->cfg.head_dim, ddev, (const AttnItem*)(dev + o_items), (int)items.size(), q, cache->k,
+                      cache->v, k_new, v_new, cache->k, cache->v, cache->pos, (int32_t)cache->tokens_seen,
+                      fuse_append ? 1 : 0, N_k, scale, out);
+  else
+    launch_attn(s, ctx->cfg.dtype, ctx->cfg.head_dim, ddev, (const AttnItem*)(dev + o_items), (int)items.size(), tile,
+                q, cache->k, cache->v, N_k, scale, out);
   HIP_TRY(ctx, hipGetLastError());
 
   for (int u = 0; u < U; ++u) {

@@ -96,6 +96,18 @@ size_t select_lds_bytes(int max_t_in);
 void launch_attn(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, const AttnItem* items,
                  int n_items, int q_tile_rows, const void* q, const void* k_cache,
                  const void* v_cache, int N_k, float scale, void* out);
+// bf16 attention for steps with few queries: work item = (unit, tile of
+// attn_split_q_tile_rows() queries), keys split over the waves of a work-group.
+// fuse == 0: attends over rows [out_off, out_off + n_out) of k_cache / v_cache.
+// fuse != 0: attends over [rows in_off .. +len_in of the cache | the unit's N_k rows
+// of k_new / v_new] (n_out = len_in + N_k) and also writes those rows (and their
+// positions pos_new + row, if pos_app != nullptr) behind the cached ones in
+// k_app / v_app / pos_app, i.e. it performs the append of the step as well.
+int attn_split_q_tile_rows();
+void launch_attn_split(hipStream_t s, int head_dim, const UnitDesc* descs, const AttnItem* items, int n_items,
+                       const void* q, const void* k_cache, const void* v_cache, const void* k_new, const void* v_new,
+                       void* k_app, void* v_app, int32_t* pos_app, int pos_new, int fuse, int N_k, float scale,
+                       void* out);
 // Attention variance of the listed units (bf16): sigma[desc.unit] = sum over the
 // unit's n_out keys of the population variance, across its N_k queries, of the
 // softmax probabilities.  stats: workspace of 2 floats per (unit, query).

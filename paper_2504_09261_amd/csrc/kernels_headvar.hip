@@ -24,7 +24,10 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
 constexpr int kThreads = 256;          // 4 waves
-constexpr int kTile = 128;             // queries (pass 1) or keys (pass 2) per work-group: 32 per wave
+constexpr int kRB1 = 4;                // 32-query blocks per wave in pass 1
+constexpr int kRB2 = 2;                // 32-key blocks per wave in pass 2 (64 registers of fp64 sums per block)
+constexpr int kTile1 = 4 * 32 * kRB1;  // queries per work-group in pass 1
+constexpr int kTile2 = 4 * 32 * kRB2;  // keys per work-group in pass 2
 constexpr float kLog2eF = 1.4426950408889634f;
 
 __device__ __forceinline__ float pair_max(float v) {   // over the lane pair (l, l ^ 32)
@@ -70,6 +73,7 @@ __device__ __forceinline__ floatx16 scores_t(const bf16x8 (&kf)[D / 16], const b
 }
 
 // Pass 1: stats[(u*N_k + i)] = (max_j s_ij, sum_j 2^((s_ij - max) * c2)), s = raw dot product, c2 = scale*log2(e).
+// A wave owns kRB1 blocks of 32 queries, so every K fragment it fetches feeds kRB1 MFMAs.
 template <int D>
 __global__ __launch_bounds__(kThreads) void hv_rowstats(
     const UnitDesc* __restrict__ descs, const __bf16* __restrict__ q, const __bf16* __restrict__ k_cache,
@@ -77,38 +81,55 @@ __global__ __launch_bounds__(kThreads) void hv_rowstats(
   const UnitDesc d = descs[blockIdx.y];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int q0 = blockIdx.x * kTile + w * 32;
+  const int q0 = blockIdx.x * kTile1 + w * (32 * kRB1);
   if (q0 >= N_k) return;
   const int len = d.n_out;
   const __bf16* kg = k_cache + d.out_off * D;
-  bf16x8 qf[D / 16];
-  load_frags<D>(q + ((int64_t)d.unit * N_k + q0) * D, min(32, N_k - q0), lane, qf);
+  bf16x8 qf[kRB1][D / 16];
+#pragma unroll
+  for (int j = 0; j < kRB1; ++j) {
+    const int qj = min(q0 + 32 * j, N_k - 1);   // a block past the end repeats the last query; it is not stored
+    load_frags<D>(q + ((int64_t)d.unit * N_k + qj) * D, min(32, N_k - qj), lane, qf[j]);
+  }
   const float c2 = scale * kLog2eF;
-  float m = -INFINITY, l = 0.f;
+  float m[kRB1], l[kRB1];
+#pragma unroll
+  for (int j = 0; j < kRB1; ++j) {
+    m[j] = -INFINITY;
+    l[j] = 0.f;
+  }
   for (int t0 = 0; t0 < len; t0 += 32) {
     const int nv = min(32, len - t0);
     bf16x8 kf[D / 16];
     load_frags<D>(kg + (int64_t)t0 * D, nv, lane, kf);
-    floatx16 sc = scores_t<D>(kf, qf);
-    float mx = -INFINITY;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      if (c_row(r, half) >= nv) sc[r] = -INFINITY;
-      mx = fmaxf(mx, sc[r]);
+    for (int j = 0; j < kRB1; ++j) {
+      floatx16 sc = scores_t<D>(kf, qf[j]);
+      float mx = -INFINITY;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        if (c_row(r, half) >= nv) sc[r] = -INFINITY;
+        mx = fmaxf(mx, sc[r]);
+      }
+      mx = pair_max(mx);                       // finite: the block holds a valid key
+      const float m_new = fmaxf(m[j], mx);
+      float s = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s += __builtin_amdgcn_exp2f((sc[r] - m_new) * c2);
+      l[j] = l[j] * __builtin_amdgcn_exp2f((m[j] - m_new) * c2) + s;   // first block: 0 * exp2(-inf) = 0
+      m[j] = m_new;
     }
-    mx = pair_max(mx);                       // finite: the block holds a valid key
-    const float m_new = fmaxf(m, mx);
-    float s = 0.f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s += __builtin_amdgcn_exp2f((sc[r] - m_new) * c2);
-    l = l * __builtin_amdgcn_exp2f((m - m_new) * c2) + s;   // first block: l = 0 * exp2(-inf) = 0
-    m = m_new;
   }
-  l = pair_sum(l);
-  if (half == 0 && q0 + col < N_k) stats[(int64_t)d.unit * N_k + q0 + col] = make_float2(m, l);
+#pragma unroll
+  for (int j = 0; j < kRB1; ++j) {
+    const float lj = pair_sum(l[j]);
+    const int qi = q0 + 32 * j + col;
+    if (half == 0 && qi < N_k) stats[(int64_t)d.unit * N_k + qi] = make_float2(m[j], lj);
+  }
 }
 
 // Pass 2: sigma[u] += (1/N) sum_ij p_ij^2 - (1/N^2) sum_j (sum_i p_ij)^2 over this work-group's keys.
+// A wave owns kRB2 blocks of 32 keys, so every Q fragment it fetches feeds kRB2 MFMAs.
 template <int D>
 __global__ __launch_bounds__(kThreads) void hv_colmoments(
     const UnitDesc* __restrict__ descs, const __bf16* __restrict__ q, const __bf16* __restrict__ k_cache,
@@ -117,30 +138,40 @@ __global__ __launch_bounds__(kThreads) void hv_colmoments(
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int col = lane & 31, half = lane >> 5;
   const int len = d.n_out;
-  const int t0 = blockIdx.x * kTile + w * 32;
+  const int t0 = blockIdx.x * kTile2 + w * (32 * kRB2);
   if (t0 >= len) return;
-  const int nv = min(32, len - t0);
-  bf16x8 kf[D / 16];
-  load_frags<D>(k_cache + (d.out_off + t0) * D, nv, lane, kf);
+  bf16x8 kf[kRB2][D / 16];
+  int nv[kRB2];
+#pragma unroll
+  for (int j = 0; j < kRB2; ++j) {
+    const int tj = min(t0 + 32 * j, len - 1);   // a block past the end repeats the last key; nv = 0 leaves it out
+    nv[j] = max(0, min(32, len - (t0 + 32 * j)));
+    load_frags<D>(k_cache + (d.out_off + tj) * D, max(1, min(32, len - tj)), lane, kf[j]);
+  }
   const float c2 = scale * kLog2eF;
   const __bf16* qg = q + (int64_t)d.unit * N_k * D;
   const float2* st = stats + (int64_t)d.unit * N_k;
-  double c1[16], s2[16];   // per key row: sum_i p_ij and sum_i p_ij^2 over this lane's queries
+  double c1[kRB2][16], s2[kRB2][16];   // per key row: sum_i p_ij and sum_i p_ij^2 over this lane's queries
 #pragma unroll
-  for (int r = 0; r < 16; ++r) c1[r] = s2[r] = 0.0;
+  for (int j = 0; j < kRB2; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) c1[j][r] = s2[j][r] = 0.0;
   for (int q0 = 0; q0 < N_k; q0 += 32) {
     const int nq = min(32, N_k - q0);
     bf16x8 qf[D / 16];
     load_frags<D>(qg + (int64_t)q0 * D, nq, lane, qf);
     const float2 ml = st[q0 + min(col, nq - 1)];
-    const floatx16 sc = scores_t<D>(kf, qf);
     const float inv = (col < nq) ? 1.f / ml.y : 0.f;   // queries past the end contribute nothing
     const float mc = ml.x * c2;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const double p = (double)(__builtin_amdgcn_exp2f(fmaf(sc[r], c2, -mc)) * inv);
-      c1[r] += p;
-      s2[r] = fma(p, p, s2[r]);
+    for (int j = 0; j < kRB2; ++j) {
+      const floatx16 sc = scores_t<D>(kf[j], qf);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const double p = (double)(__builtin_amdgcn_exp2f(fmaf(sc[r], c2, -mc)) * inv);
+        c1[j][r] += p;
+        s2[j][r] = fma(p, p, s2[j][r]);
+      }
     }
   }
   // a half-wave holds 32 different queries of the same 16 key rows; rows past the
@@ -148,11 +179,13 @@ __global__ __launch_bounds__(kThreads) void hv_colmoments(
   const double inv_n = 1.0 / (double)N_k;
   double acc = 0.0;
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const double c = half_sum_f64(c1[r]) * inv_n;
-    const double s = half_sum_f64(s2[r]) * inv_n;
-    if (c_row(r, half) < nv) acc += s - c * c;   // Var_i(A[i, j]) of this key
-  }
+  for (int j = 0; j < kRB2; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const double c = half_sum_f64(c1[j][r]) * inv_n;
+      const double s = half_sum_f64(s2[j][r]) * inv_n;
+      if (c_row(r, half) < nv[j]) acc += s - c * c;   // Var_i(A[i, j]) of this key
+    }
   if (col == 0) atomicAdd(&sigma[d.unit], acc);
 }
 
@@ -168,7 +201,7 @@ void launch_head_variance(hipStream_t s, int head_dim, const UnitDesc* descs, in
   if (n_desc <= 0) return;
   typedef __bf16 T;
   hipLaunchKernelGGL(hv_zero, dim3((n_desc + 63) / 64), dim3(64), 0, s, descs, n_desc, sigma);
-  const dim3 g1((N_k + kTile - 1) / kTile, n_desc), g2((max_len + kTile - 1) / kTile, n_desc);
+  const dim3 g1((N_k + kTile1 - 1) / kTile1, n_desc), g2((max_len + kTile2 - 1) / kTile2, n_desc);
   if (head_dim == 64) {
     hipLaunchKernelGGL(hv_rowstats<64>, g1, dim3(kThreads), 0, s, descs, (const T*)q, (const T*)k_cache, N_k, scale,
                        (float2*)stats);

@@ -54,11 +54,25 @@ def build_cache(rows_per_unit, d, dtype, pad_rows=0, fill=None):
 
 
 def make_hack(cfg_or_none=None, *, heads=None, head_dim=None, dtype=None, max_units=None, max_cache_len=None,
-              max_queries=None, n_obs=32) -> Hack:
-    if cfg_or_none is not None:
-        c = cfg_or_none
-        return Hack(c.heads, c.head_dim, c.dtype, c.n_units, c.T_K, max(c.N), c.n_obs)
-    return Hack(heads, head_dim, dtype, max_units, max_cache_len, max_queries, n_obs)
+              max_queries=None, n_obs=32, attention=None) -> Hack:
+    """attention: None = the library's own choice between its two bf16 attention kernels per launch;
+    "split" / "tile128" = force the key-split (32-query items) or the 128-query-tile kernel for every
+    launch of this context (the library reads the override when the context is created)."""
+    import os
+    saved = os.environ.get("HACK_ATTN_SPLIT_ITEMS")
+    if attention is not None:
+        os.environ["HACK_ATTN_SPLIT_ITEMS"] = {"split": "2000000000", "tile128": "0"}[attention]
+    try:
+        if cfg_or_none is not None:
+            c = cfg_or_none
+            return Hack(c.heads, c.head_dim, c.dtype, c.n_units, c.T_K, max(c.N), c.n_obs)
+        return Hack(heads, head_dim, dtype, max_units, max_cache_len, max_queries, n_obs)
+    finally:
+        if attention is not None:
+            if saved is None:
+                del os.environ["HACK_ATTN_SPLIT_ITEMS"]
+            else:
+                os.environ["HACK_ATTN_SPLIT_ITEMS"] = saved
 
 
 def kept_set_verdict(I_gpu: np.ndarray, I_ref: np.ndarray, imp_ref: np.ndarray, sel_lo: int, sel_hi: int, m: int):

@@ -316,19 +316,28 @@ def test_score_cache_only_custom_rows_and_inactive_units():
 # ---------------------------------------------------------------------------
 # a4 attention
 # ---------------------------------------------------------------------------
-@pytest.mark.parametrize("dtype,d,Nk,lens,tol", [
-    ("bf16", 128, 300, [1, 2, 63, 64, 65, 1943, 127, 700], 2e-2),
-    ("bf16", 64, 100, [102, 306, 1, 33, 562, 91, 128, 129], 2e-2),
-    ("bf16", 128, 1, [1, 5, 21, 57, 121, 265, 64, 32], 2e-2),
-    ("f32", 64, 100, [102, 306, 1, 33, 562, 91, 128, 129], 1e-4),
-    ("f32", 128, 70, [1, 2, 63, 64, 65, 300, 127, 31], 1e-4),
+@pytest.mark.parametrize("dtype,d,Nk,lens,tol,kernel", [
+    ("bf16", 128, 300, [1, 2, 63, 64, 65, 1943, 127, 700], 2e-2, "tile128"),
+    ("bf16", 128, 300, [1, 2, 63, 64, 65, 1943, 127, 700], 2e-2, "split"),
+    ("bf16", 64, 100, [102, 306, 1, 33, 562, 91, 128, 129], 2e-2, "tile128"),
+    ("bf16", 64, 100, [102, 306, 1, 33, 562, 91, 128, 129], 2e-2, "split"),
+    ("bf16", 128, 1, [1, 5, 21, 57, 121, 265, 64, 32], 2e-2, "tile128"),
+    ("bf16", 128, 1, [1, 5, 21, 57, 121, 265, 64, 32], 2e-2, "split"),
+    ("bf16", 64, 33, [3, 31, 32, 96, 97, 160, 2000, 129], 2e-2, "split"),
+    ("bf16", 128, 300, [1, 2, 63, 64, 65, 1943, 127, 700], 2e-2, None),
+    ("f32", 64, 100, [102, 306, 1, 33, 562, 91, 128, 129], 1e-4, None),
+    ("f32", 128, 70, [1, 2, 63, 64, 65, 300, 127, 31], 1e-4, None),
 ])
-def test_attention_matches_oracle(dtype, d, Nk, lens, tol):
+def test_attention_matches_oracle(dtype, d, Nk, lens, tol, kernel):
+    """Both bf16 attention kernels (128-query tiles; 32-query items with the keys split
+    over the waves) on the same ragged shapes: fewer keys than waves, one key, block
+    boundaries +-1, many blocks per wave, a last query tile with a single query."""
     u = _u()
     rng = np.random.default_rng(17 + Nk + d)
     H, B = 4, 2
     U = H * B
-    hk = u.make_hack(heads=H, head_dim=d, dtype=dtype, max_units=U, max_cache_len=2048, max_queries=512)
+    hk = u.make_hack(heads=H, head_dim=d, dtype=dtype, max_units=U, max_cache_len=2048, max_queries=512,
+                     attention=kernel)
     scale = float(np.float32(1.0 / np.sqrt(d)))
     rows = [(u.rand_values(rng, (n, d), dtype) * 1.5, u.rand_values(rng, (n, d), dtype)) for n in lens]
     if dtype == "bf16":

@@ -21,10 +21,10 @@ def _tol(cfg):
     return 1e-4 if cfg.dtype == "f32" else 2e-2
 
 
-def run_free(cfg, layer, units, steps=None, types=None):
+def run_free(cfg, layer, units, steps=None, types=None, attention=None):
     """hack_step over the schedule on all units; oracle on `units`.  Returns statistics."""
     u = _u()
-    hk = u.make_hack(cfg)
+    hk = u.make_hack(cfg, attention=attention)
     types = wl.head_types(cfg, layer) if types is None else np.asarray(types, np.uint8)
     cap = np.minimum(np.tile(wl.head_budgets(cfg, layer), cfg.batch), cfg.T_K)
     mc = hk.managed_cache(cap)
@@ -127,6 +127,22 @@ def test_swapped_policies_and_single_class_masks():
     for types in (1 - planted, np.zeros_like(planted), np.ones_like(planted)):
         stats = run_free(cfg, 0, list(range(0, cfg.n_units, 3)), types=types)
         assert stats["mismatch"] == 0 and stats["compress_events"] > 0
+
+
+@pytest.mark.parametrize("attention", ["split", "tile128"])
+def test_schedule_with_either_attention_kernel_forced(attention):
+    """hack_step picks the attention kernel per step (key-split with the append fused
+    into it for steps with few queries, 128-query tiles after a separate append
+    otherwise).  Forcing one kernel for every step covers the combinations the
+    default choice does not reach at these sizes: the key-split kernel after a
+    gather and on long caches, the tiled kernel on the smallest steps.  Outputs,
+    kept sets, positions and the final cache contents are checked as usual."""
+    cfg = wl.get_config(1, batch=1)
+    stats = run_free(cfg, 0, list(range(0, cfg.n_units, 4)), attention=attention)
+    assert stats["mismatch"] == 0 and stats["compress_events"] > 0
+    cfg = wl.get_config(4, keep=0.5, ctx_frac=0.25, batch=1)
+    stats = run_free(cfg, 2, [0, 3, 5, 11], steps=11, attention=attention)
+    assert stats["mismatch"] == 0 and stats["compress_events"] > 0
 
 
 def test_cfg4_ragged_budgets_small_batch():
