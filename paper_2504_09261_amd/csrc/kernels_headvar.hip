@@ -9,11 +9,14 @@
 // the scores tile by tile, turns them into probabilities and accumulates the sum
 // of squares and each key's column sum.
 //
-// This is an offline step (run once per model on a small validation set), so the
-// kernels are kept simple: S^T = K Q^T with v_mfma_f32_32x32x16_bf16 (a lane then
-// owns one query column and 16 key rows), operands straight from global memory /
-// L2, no LDS staging, no work-group barriers.  The sums that are subtracted from
-// each other are kept in fp64.
+// Both passes stream one operand (the keys in pass 1, the queries in pass 2) in
+// 32-row blocks HBM -> LDS (global_load_lds, coalesced whole rows) through a ring
+// shared by the four waves of a work-group, one barrier per block, and keep the
+// other operand in registers: S^T = K Q^T with v_mfma_f32_32x32x16_bf16, so a
+// lane owns one query column and 16 key rows.  (Fetching MFMA operands straight
+// from global memory, one row per lane, runs the memory pipeline at a quarter of
+// its coalesced rate.)  The sums that are subtracted from each other are kept in
+// fp64.
 #include "hack_internal.h"
 
 namespace hack {
@@ -24,11 +27,80 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
 constexpr int kThreads = 256;          // 4 waves
-constexpr int kRB1 = 4;                // 32-query blocks per wave in pass 1
+constexpr int kWaves = 4;
+constexpr int kRB1 = 2;                // 32-query blocks per wave in pass 1
 constexpr int kRB2 = 2;                // 32-key blocks per wave in pass 2 (64 registers of fp64 sums per block)
-constexpr int kTile1 = 4 * 32 * kRB1;  // queries per work-group in pass 1
-constexpr int kTile2 = 4 * 32 * kRB2;  // keys per work-group in pass 2
+constexpr int kTile1 = kWaves * 32 * kRB1;  // queries per work-group in pass 1
+constexpr int kTile2 = kWaves * 32 * kRB2;  // keys per work-group in pass 2
+constexpr int kRing = 4;               // LDS ring slots (32-row blocks)
 constexpr float kLog2eF = 1.4426950408889634f;
+
+// 16-byte chunk c of LDS row r holds global chunk c ^ swz(r): b128 operand reads
+// (16 rows at one chunk position per phase) stay free of bank conflicts on the
+// 64-bank LDS, although rows cannot be padded (a copy instruction fills one
+// contiguous KiB).
+template <int D> __device__ __forceinline__ int swz(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
+
+// HBM -> LDS copies, issued from inline assembly so that the compiler does not
+// drain them before unrelated LDS reads; dma_wait_but<N>() is the matching wait
+// (copies complete in order: all but the newest N instructions have landed).
+// base: wave-uniform address; voff: this lane's byte offset; lds_addr:
+// wave-uniform LDS byte address (lane l writes [16 l, +16) resp. [4 l, +4)).
+__device__ __forceinline__ void load_to_lds_x4(const void* base, unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_addr) : "memory", "m0");
+}
+__device__ __forceinline__ void load_to_lds_x1(const void* base, unsigned voff, unsigned lds_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(voff), "s"(base), "s"(lds_addr) : "memory", "m0");
+}
+template <int N> __device__ __forceinline__ void dma_wait_but() {
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+  __builtin_amdgcn_sched_barrier(0);
+}
+__device__ __forceinline__ unsigned lds_addr_of(const void* p) {
+  return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
+}
+
+// Streams the 32-row blocks of a row-major [n_rows, D] bf16 matrix into an LDS
+// ring of kRing slots; the four waves of the work-group each copy a quarter of
+// a block (IPW instructions).  Rows past the end repeat the last row.
+template <int D>
+struct BlockStream {
+  static constexpr int CPR = D / 8;               // 16-byte chunks per row
+  static constexpr int RPI = 64 / CPR;            // rows per copy instruction
+  static constexpr int IPW = (32 / RPI) / kWaves; // copy instructions per wave and block
+  static constexpr int BLK = 32 * D;              // elements per block
+  const __bf16* base;
+  int n_rows, lane, w;
+  unsigned lds0;
+  unsigned src[IPW];
+  __device__ __forceinline__ void init(const __bf16* base_, int n_rows_, const __bf16* ring, int lane_, int w_) {
+    base = base_; n_rows = n_rows_; lane = lane_; w = w_;
+    lds0 = lds_addr_of(ring);
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) {
+      const int r = (w + i * kWaves) * RPI + lane / CPR, c = lane % CPR;
+      src[i] = (unsigned)(r * D + ((c ^ swz<D>(r)) & (CPR - 1)) * 8) * 2u;
+    }
+  }
+  __device__ __forceinline__ void issue(int b, int slot) const {
+    const int r0 = b * 32;
+    const __bf16* blk = base + (int64_t)r0 * D;
+    if (r0 + 32 <= n_rows) {
+#pragma unroll
+      for (int i = 0; i < IPW; ++i)
+        load_to_lds_x4(blk, src[i], lds0 + (unsigned)((slot * BLK + (w + i * kWaves) * 512) * 2));
+    } else {
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        const int r = (w + i * kWaves) * RPI + lane / CPR, c = lane % CPR;
+        const int rc = min(r, n_rows - 1 - r0);
+        load_to_lds_x4(blk, (unsigned)(rc * D + ((c ^ swz<D>(r)) & (CPR - 1)) * 8) * 2u,
+                       lds0 + (unsigned)((slot * BLK + (w + i * kWaves) * 512) * 2));
+      }
+    }
+  }
+};
 
 __device__ __forceinline__ float pair_max(float v) {   // over the lane pair (l, l ^ 32)
   return fmaxf(v, __shfl_xor(v, 32, 64));
@@ -72,24 +144,41 @@ __device__ __forceinline__ floatx16 scores_t(const bf16x8 (&kf)[D / 16], const b
   return sc;
 }
 
-// Pass 1: stats[(u*N_k + i)] = (max_j s_ij, sum_j 2^((s_ij - max) * c2)), s = raw dot product, c2 = scale*log2(e).
-// A wave owns kRB1 blocks of 32 queries, so every K fragment it fetches feeds kRB1 MFMAs.
+// Operand fragment kk of the block in an LDS slot: row lane%32, chunk 2kk + lane/32
 template <int D>
-__global__ __launch_bounds__(kThreads) void hv_rowstats(
+__device__ __forceinline__ bf16x8 lds_frag(const __bf16* slot, int col, int half, int kk) {
+  constexpr int CPR = D / 8;
+  return *reinterpret_cast<const bf16x8*>(&slot[col * D + (((2 * kk + half) ^ swz<D>(col)) & (CPR - 1)) * 8]);
+}
+
+// Pass 1: stats[(u*N_k + i)] = (max_j s_ij, sum_j 2^((s_ij - max) * c2)), s = raw dot product, c2 = scale*log2(e).
+// A wave owns kRB1 blocks of 32 queries (registers); the keys stream through LDS.
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void hv_rowstats(
     const UnitDesc* __restrict__ descs, const __bf16* __restrict__ q, const __bf16* __restrict__ k_cache,
     int N_k, float scale, float2* __restrict__ stats) {
+  using St = BlockStream<D>;
+  constexpr int KK = D / 16;
+  __shared__ __attribute__((aligned(1024))) __bf16 ring[kRing][St::BLK];
   const UnitDesc d = descs[blockIdx.y];
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 31, half = lane >> 5;
-  const int q0 = blockIdx.x * kTile1 + w * (32 * kRB1);
-  if (q0 >= N_k) return;
+  const int q0 = blockIdx.x * kTile1 + w * (32 * kRB1);   // may lie past N_k: the wave still copies and synchronises
   const int len = d.n_out;
-  const __bf16* kg = k_cache + d.out_off * D;
-  bf16x8 qf[kRB1][D / 16];
+  const int n_blocks = (len + 31) / 32;
+  St st;
+  st.init(k_cache + d.out_off * D, len, &ring[0][0], lane, w);
+  st.issue(0, 0);
+  if (n_blocks > 1) st.issue(1, 1);
+
+  bf16x8 qf[kRB1][KK];
 #pragma unroll
   for (int j = 0; j < kRB1; ++j) {
-    const int qj = min(q0 + 32 * j, N_k - 1);   // a block past the end repeats the last query; it is not stored
+    // a block past the end repeats the last query; it is not stored
+    const int qj = min(q0 + 32 * j, N_k - 1);
     load_frags<D>(q + ((int64_t)d.unit * N_k + qj) * D, min(32, N_k - qj), lane, qf[j]);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) asm volatile("" ::"v"(qf[j][kk]));   // waited for here, not inside the loop
   }
   const float c2 = scale * kLog2eF;
   float m[kRB1], l[kRB1];
@@ -98,25 +187,34 @@ __global__ __launch_bounds__(kThreads) void hv_rowstats(
     m[j] = -INFINITY;
     l[j] = 0.f;
   }
-  for (int t0 = 0; t0 < len; t0 += 32) {
-    const int nv = min(32, len - t0);
-    bf16x8 kf[D / 16];
-    load_frags<D>(kg + (int64_t)t0 * D, nv, lane, kf);
+  for (int b = 0; b < n_blocks; ++b) {
+    if (b + 1 < n_blocks) dma_wait_but<St::IPW>();   // this wave's part of block b has landed
+    else dma_wait_but<0>();
+    __syncthreads();                                  // all of block b is visible; the slot of block b-2 is free
+    if (b + 2 < n_blocks) st.issue(b + 2, (b + 2) % kRing);
+    const __bf16* slot = &ring[b % kRing][0];
+    const int nv = min(32, len - b * 32);
+    bf16x8 kf[KK];
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) kf[kk] = lds_frag<D>(slot, col, half, kk);
 #pragma unroll
     for (int j = 0; j < kRB1; ++j) {
       floatx16 sc = scores_t<D>(kf, qf[j]);
-      float mx = -INFINITY;
+      if (nv < 32) {                           // only the unit's last block is ragged
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        if (c_row(r, half) >= nv) sc[r] = -INFINITY;
-        mx = fmaxf(mx, sc[r]);
+        for (int r = 0; r < 16; ++r)
+          if (c_row(r, half) >= nv) sc[r] = -INFINITY;
       }
+      float mx = sc[0];
+#pragma unroll
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
       mx = pair_max(mx);                       // finite: the block holds a valid key
       const float m_new = fmaxf(m[j], mx);
+      const float mc = m_new * c2;
       float s = 0.f;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s += __builtin_amdgcn_exp2f((sc[r] - m_new) * c2);
-      l[j] = l[j] * __builtin_amdgcn_exp2f((m[j] - m_new) * c2) + s;   // first block: 0 * exp2(-inf) = 0
+      for (int r = 0; r < 16; ++r) s += __builtin_amdgcn_exp2f(fmaf(sc[r], c2, -mc));
+      l[j] = l[j] * __builtin_amdgcn_exp2f(fmaf(m[j], c2, -mc)) + s;   // first block: 0 * exp2(-inf) = 0
       m[j] = m_new;
     }
   }
@@ -129,46 +227,82 @@ __global__ __launch_bounds__(kThreads) void hv_rowstats(
 }
 
 // Pass 2: sigma[u] += (1/N) sum_ij p_ij^2 - (1/N^2) sum_j (sum_i p_ij)^2 over this work-group's keys.
-// A wave owns kRB2 blocks of 32 keys, so every Q fragment it fetches feeds kRB2 MFMAs.
+// A wave owns kRB2 blocks of 32 keys (registers); the queries and their pass-1
+// statistics stream through LDS (every wave copies the 256 bytes of statistics
+// of a block itself, so all waves issue the same number of copies per block).
 template <int D>
-__global__ __launch_bounds__(kThreads) void hv_colmoments(
+__global__ __launch_bounds__(kThreads, 2) void hv_colmoments(
     const UnitDesc* __restrict__ descs, const __bf16* __restrict__ q, const __bf16* __restrict__ k_cache,
     int N_k, float scale, const float2* __restrict__ stats, double* __restrict__ sigma) {
+  using St = BlockStream<D>;
+  constexpr int KK = D / 16;
+  __shared__ __attribute__((aligned(1024))) __bf16 ring[kRing][St::BLK];
+  __shared__ __attribute__((aligned(256))) float2 st_ring[kRing][kWaves][32];
   const UnitDesc d = descs[blockIdx.y];
-  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = lane & 31, half = lane >> 5;
   const int len = d.n_out;
+  if ((int)blockIdx.x * kTile2 >= len) return;   // whole work-group past the end of this unit
   const int t0 = blockIdx.x * kTile2 + w * (32 * kRB2);
-  if (t0 >= len) return;
-  bf16x8 kf[kRB2][D / 16];
+  const int n_blocks = (N_k + 31) / 32;
+  St st;
+  st.init(q + (int64_t)d.unit * N_k * D, N_k, &ring[0][0], lane, w);
+  const float* stat_base = reinterpret_cast<const float*>(stats + (int64_t)d.unit * N_k);
+  const unsigned st_lds = lds_addr_of(&st_ring[0][0][0]);
+  // block b of the queries and its statistics: lane l copies float l of the
+  // block's 64 (a query past the end repeats the last one; it is masked below)
+  auto issue = [&](int b, int slot) {
+    st.issue(b, slot);
+    const int qi = min(b * 32 + (lane >> 1), N_k - 1);
+    load_to_lds_x1(stat_base, (unsigned)(qi * 2 + (lane & 1)) * 4u, st_lds + (unsigned)((slot * kWaves + w) * 256));
+  };
+  issue(0, 0);
+  if (n_blocks > 1) issue(1, 1);
+
+  // a wave whose keys all lie past the end of the unit still takes part in the copies and barriers
+  bf16x8 kf[kRB2][KK];
   int nv[kRB2];
 #pragma unroll
   for (int j = 0; j < kRB2; ++j) {
     const int tj = min(t0 + 32 * j, len - 1);   // a block past the end repeats the last key; nv = 0 leaves it out
     nv[j] = max(0, min(32, len - (t0 + 32 * j)));
     load_frags<D>(k_cache + (d.out_off + tj) * D, max(1, min(32, len - tj)), lane, kf[j]);
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) asm volatile("" ::"v"(kf[j][kk]));   // waited for here, not inside the loop
   }
   const float c2 = scale * kLog2eF;
-  const __bf16* qg = q + (int64_t)d.unit * N_k * D;
-  const float2* st = stats + (int64_t)d.unit * N_k;
   double c1[kRB2][16], s2[kRB2][16];   // per key row: sum_i p_ij and sum_i p_ij^2 over this lane's queries
 #pragma unroll
   for (int j = 0; j < kRB2; ++j)
 #pragma unroll
     for (int r = 0; r < 16; ++r) c1[j][r] = s2[j][r] = 0.0;
-  for (int q0 = 0; q0 < N_k; q0 += 32) {
-    const int nq = min(32, N_k - q0);
-    bf16x8 qf[D / 16];
-    load_frags<D>(qg + (int64_t)q0 * D, nq, lane, qf);
-    const float2 ml = st[q0 + min(col, nq - 1)];
-    const float inv = (col < nq) ? 1.f / ml.y : 0.f;   // queries past the end contribute nothing
-    const float mc = ml.x * c2;
+  for (int b = 0; b < n_blocks; ++b) {
+    if (b + 1 < n_blocks) dma_wait_but<St::IPW + 1>();   // this wave's copies of block b have landed
+    else dma_wait_but<0>();
+    __syncthreads();                                      // all of block b is visible; the slot of block b-2 is free
+    if (b + 2 < n_blocks) issue(b + 2, (b + 2) % kRing);
+    const __bf16* slot = &ring[b % kRing][0];
+    const int nq = min(32, N_k - b * 32);
+    const float2 ml = st_ring[b % kRing][w][col];
+    // p = 2^(s c2 - (m c2 + log2 l)): the normaliser rides in the exponent; queries past the end give 2^-inf = 0
+    const float mc = (col < nq) ? fmaf(ml.x, c2, __builtin_amdgcn_logf(ml.y)) : INFINITY;
+    // every query fragment feeds the MFMAs of all kRB2 key blocks and is then dropped
+    floatx16 sc[kRB2];
+#pragma unroll
+    for (int j = 0; j < kRB2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) sc[j][r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) {
+      const bf16x8 qf = lds_frag<D>(slot, col, half, kk);
+#pragma unroll
+      for (int j = 0; j < kRB2; ++j) sc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[j][kk], qf, sc[j], 0, 0, 0);
+    }
 #pragma unroll
     for (int j = 0; j < kRB2; ++j) {
-      const floatx16 sc = scores_t<D>(kf[j], qf);
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const double p = (double)(__builtin_amdgcn_exp2f(fmaf(sc[r], c2, -mc)) * inv);
+        const double p = (double)__builtin_amdgcn_exp2f(fmaf(sc[j][r], c2, -mc));
         c1[j][r] += p;
         s2[j][r] = fma(p, p, s2[j][r]);
       }
@@ -186,7 +320,7 @@ __global__ __launch_bounds__(kThreads) void hv_colmoments(
       const double s = half_sum_f64(s2[j][r]) * inv_n;
       if (c_row(r, half) < nv[j]) acc += s - c * c;   // Var_i(A[i, j]) of this key
     }
-  if (col == 0) atomicAdd(&sigma[d.unit], acc);
+  if (col == 0 && t0 < len) atomicAdd(&sigma[d.unit], acc);
 }
 
 __global__ void hv_zero(const UnitDesc* __restrict__ descs, int n, double* __restrict__ sigma) {
