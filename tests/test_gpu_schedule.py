@@ -293,3 +293,63 @@ def test_graph_replays_reproduce_the_eager_schedule():
             assert torch.equal(ref[4][o:o + n], got[4][o:o + n]) and torch.equal(ref[5][o:o + n], got[5][o:o + n])
     mc.close()
     hk.close()
+
+
+def test_largest_supported_cache_through_individual_calls():
+    """One contextual and one structural unit at the library's limit, T_in = 32768 rows (the
+    selection keeps a unit's keys in LDS): score, select, compact, attend, each against the oracle;
+    one row more is refused."""
+    u = _u()
+    from paper_2504_09261_amd.binding import HackError
+    rng = np.random.default_rng(32768)
+    H, d, dtype, T_max, Nk, n_init = 2, 128, "bf16", 32768, 300, 5
+    L = T_max - Nk
+    hk = u.make_hack(heads=H, head_dim=d, dtype=dtype, max_units=H, max_cache_len=T_max, max_queries=Nk)
+    scale = float(np.float32(1.0 / np.sqrt(d)))
+    types = np.array([0, 1], np.uint8)
+    budget = np.array([9001, 20003], np.int32)
+    rows = [(u.rand_values(rng, (L, d), dtype), u.rand_values(rng, (L, d), dtype)) for _ in range(H)]
+    cin, _ = u.build_cache(rows, d, dtype)
+    q, kn, vn = (u.rand_values(rng, (1, H, Nk, d), dtype) for _ in range(3))
+    qd, knd, vnd = u.to_dev(q, dtype), u.to_dev(kn, dtype), u.to_dev(vn, dtype)
+    stride = T_max
+    imp = torch.zeros((H, stride), device=u.DEV)
+    hk.score(qd, cin, scale, imp, k_new=knd)
+    torch.cuda.synchronize()
+    hk.check()
+    imp_h = imp.cpu().numpy()
+    obs = ho.observation_rows(Nk, 32)
+    imp_ref = np.zeros((H, stride), np.float32)
+    K_in, V_in = [], []
+    for uu in range(H):
+        K_in.append(np.concatenate([rows[uu][0], kn[0, uu]]).astype(np.float64))
+        V_in.append(np.concatenate([rows[uu][1], vn[0, uu]]).astype(np.float64))
+        ref = ho.importance(q[0, uu][obs].astype(np.float64), K_in[uu], scale)
+        assert float(np.max(np.abs(imp_h[uu] - ref) / ref)) < 1e-6, uu
+        imp_ref[uu] = ref.astype(np.float32)
+    kept = torch.full((H, stride), -1, dtype=torch.int32, device=u.DEV)
+    t_in = np.full(H, T_max, np.int32)
+    len_out = hk.select(1, torch.from_numpy(imp_ref).to(u.DEV), t_in, types, budget, n_init, Nk, kept)
+    torch.cuda.synchronize()
+    kept_h = kept.cpu().numpy()
+    want_I = [ho.select(imp_ref[uu].astype(np.float64), int(types[uu]), int(budget[uu]), n_init, Nk) for uu in range(H)]
+    for uu in range(H):
+        assert len_out[uu] == budget[uu] and np.array_equal(kept_h[uu, :len_out[uu]], want_I[uu]), uu
+    off_out, total = u.aligned_offsets(len_out)
+    cout = Cache(torch.zeros((total, d), dtype=hk.torch_dtype, device=u.DEV),
+                 torch.zeros((total, d), dtype=hk.torch_dtype, device=u.DEV), off_out, len_out)
+    hk.compact(1, Nk, cin, kept, cout, knd, vnd)
+    out = torch.empty_like(qd)
+    hk.attn(qd, cout, scale, out)
+    torch.cuda.synchronize()
+    Kc, Vc, got = u.from_dev(cout.k), u.from_dev(cout.v), u.from_dev(out)
+    for uu in range(H):
+        Kw, Vw = ho.compact(K_in[uu], V_in[uu], want_I[uu])
+        sl = slice(off_out[uu], off_out[uu] + len_out[uu])
+        assert np.array_equal(Kc[sl], Kw) and np.array_equal(Vc[sl], Vw), uu
+        assert np.abs(got[0, uu] - ho.attention(q[0, uu].astype(np.float64), Kw, Vw, scale)).max() < 2e-2, uu
+    # T_in = 32769: one new row too many for the context
+    q1 = torch.zeros((1, H, Nk + 1, d), dtype=hk.torch_dtype, device=u.DEV)
+    with pytest.raises(HackError):
+        hk.score(q1, cin, scale, imp, k_new=q1)
+    hk.close()
