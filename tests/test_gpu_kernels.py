@@ -369,3 +369,20 @@ def test_attention_rejects_empty_unit_and_bad_scale():
     with pytest.raises(HackError):
         hk.attn(torch.zeros((1, 1, 9, 64), dtype=torch.bfloat16, device=u.DEV), Cache(K, K.clone(), [0], [8]), 0.1, q)
     hk.close()
+
+
+def test_attention_variant_query_matches_the_documented_rule():
+    u = _u()
+    hk = u.make_hack(heads=16, head_dim=128, dtype="bf16", max_units=32, max_cache_len=256, max_queries=4096)
+    # 32-query work items of a launch: B*H*ceil(N_k/32); the key-split kernel serves launches up to 512 of them at d = 128
+    assert [hk.attn_variant(2, n) for n in (1, 64, 400, 512, 513, 576, 4096)] == [1, 1, 1, 1, 0, 0, 0]
+    assert hk.attn_variant(1, 1024) == 1 and hk.attn_variant(1, 1025) == 0
+    hk.close()
+    hk = u.make_hack(heads=30, head_dim=64, dtype="bf16", max_units=960, max_cache_len=256, max_queries=256)
+    assert hk.attn_variant(32, 64) == 1 and hk.attn_variant(32, 100) == 0     # 1920 and 3840 items against 2048 at d = 64
+    hk.close()
+    hk = u.make_hack(heads=2, head_dim=64, dtype="f32", max_units=2, max_cache_len=64, max_queries=16)
+    assert hk.attn_variant(1, 1) == 0                                          # fp32 contexts have one attention kernel
+    with pytest.raises(HackError):
+        hk.attn_variant(0, 4)
+    hk.close()

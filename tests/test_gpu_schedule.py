@@ -229,15 +229,19 @@ def test_step_capacity_and_argument_errors():
     hk.close()
 
 
-def test_graph_replays_reproduce_the_eager_schedule():
+@pytest.mark.parametrize("attention", [None, "tile128"])
+def test_graph_replays_reproduce_the_eager_schedule(attention):
     """The whole schedule captured in a HIP graph (as bench.py launches it) is
     replayed several times, with eager work and synchronisations in between;
     every replay must reproduce the eager outputs, kept indices and final cache
-    bit for bit (the kernels' workspaces have to come back clean every time)."""
+    bit for bit (the kernels' workspaces have to come back clean every time).
+    At this size the library's own choice sends every step to the key-split
+    attention kernel with the append fused in; the second case captures the
+    128-query kernel and the separate append launches instead."""
     u = _u()
     cfg = wl.get_config(1, batch=2)
     layer = 0
-    hk = u.make_hack(cfg)
+    hk = u.make_hack(cfg, attention=attention)
     types = wl.head_types(cfg, layer)
     cap = np.minimum(np.tile(wl.head_budgets(cfg, layer), cfg.batch), cfg.T_K)
     mc = hk.managed_cache(cap)
