@@ -39,6 +39,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-breakdown", action="store_true")
     ap.add_argument("--batch", type=int, default=None)
+    ap.add_argument("--keep", type=float, default=None,
+                    help="configs 2 and 4: retained fraction of the cache averaged over heads (default 0.3, i.e. rho = 70 %%)")
     ap.add_argument("--head-variance", action="store_true",
                     help="also time the offline head-classification kernels (attention variance of every unit at the "
                          "final step over the full cache) and report them in a head_variance object")
@@ -261,7 +263,7 @@ def main():
         print(json.dumps({"mode": "copy", "launches": args.steps, "bytes_read_per_launch": 4 * n,
                           "bytes_written_per_launch": 4 * n}))
         return
-    cfg = wl.get_config(args.config, batch=args.batch)
+    cfg = wl.get_config(args.config, batch=args.batch, **({} if args.keep is None else {"keep": args.keep}))
     hk = Hack(cfg.heads, cfg.head_dim, cfg.dtype, cfg.n_units, cfg.T_K, max(cfg.N), cfg.n_obs)
     layers = [LayerState(hk, cfg, l, wl, torch, args.full_budget) for l in range(args.layers)]
 
