@@ -357,3 +357,63 @@ def test_largest_supported_cache_through_individual_calls():
     with pytest.raises(HackError):
         hk.score(q1, cin, scale, imp, k_new=q1)
     hk.close()
+
+
+@pytest.mark.parametrize("n_obs", [1, 8, 16])
+def test_observation_window_sweep_through_the_whole_schedule(n_obs):
+    """The number of observation queries is a context parameter (the paper sweeps it in
+    its ablation of the observation window): other values than 32 go through the
+    same kernels and must match the oracle run with the same value."""
+    import dataclasses
+    cfg = dataclasses.replace(wl.get_config(1, batch=1), n_obs=n_obs)
+    stats = run_free(cfg, 0, list(range(0, cfg.n_units, 5)))
+    assert stats["mismatch"] == 0 and stats["compress_events"] > 0
+
+
+def test_query_subset_variants_and_position_only_baseline():
+    """Variants of the paper's ablations expressed through the existing arguments:
+    observation queries taken from the first rows, the last rows or a random subset of
+    the current scale instead of the evenly strided ones (q_idx of hack_score), and the
+    position-only baseline (initial rows + current scale, no ranked rows) as a structural
+    head whose budget is exactly N_init + N_k."""
+    u = _u()
+    rng = np.random.default_rng(77)
+    H, d, dtype, Nk, L, n_init = 2, 128, "bf16", 256, 1500, 5
+    hk = u.make_hack(heads=H, head_dim=d, dtype=dtype, max_units=H, max_cache_len=2048, max_queries=Nk)
+    scale = float(np.float32(1.0 / np.sqrt(d)))
+    rows = [(u.rand_values(rng, (L, d), dtype) * 1.5, u.rand_values(rng, (L, d), dtype)) for _ in range(H)]
+    rows = [(wl.bf16_to_f32(wl.bf16_round(k)), v) for k, v in rows]
+    cin, _ = u.build_cache(rows, d, dtype)
+    q, kn = u.rand_values(rng, (1, H, Nk, d), dtype), u.rand_values(rng, (1, H, Nk, d), dtype)
+    qd, knd = u.to_dev(q, dtype), u.to_dev(kn, dtype)
+    T = L + Nk
+    stride = 2048
+    types = np.array([0, 1], np.uint8)
+    budget = np.array([600, 900], np.int32)
+    subsets = {"first": np.arange(32), "last": np.arange(Nk - 32, Nk),
+               "random": np.sort(rng.choice(Nk, 32, replace=False))}
+    for name, idx in subsets.items():
+        imp = torch.zeros((H, stride), device=u.DEV)
+        hk.score(qd, cin, scale, imp, k_new=knd, q_idx=idx.astype(np.int32), n_obs=32)
+        kept = torch.full((H, stride), -1, dtype=torch.int32, device=u.DEV)
+        len_out = hk.select(1, imp, np.full(H, T, np.int32), types, budget, n_init, Nk, kept)
+        torch.cuda.synchronize()
+        imp_h, kept_h = imp.cpu().numpy(), kept.cpu().numpy()
+        for uu in range(H):
+            K_in = np.concatenate([rows[uu][0], kn[0, uu]]).astype(np.float64)
+            ref = ho.importance(q[0, uu][idx].astype(np.float64), K_in, scale)
+            assert float(np.max(np.abs(imp_h[uu, :T] - ref) / ref)) < 1e-6, (name, uu)
+            I_ref = ho.select(ref, int(types[uu]), int(budget[uu]), n_init, Nk)
+            lo, hi, m = u.ranked_segment(int(types[uu]), T, int(budget[uu]), n_init, Nk)
+            assert u.kept_set_verdict(kept_h[uu, :len_out[uu]], I_ref, ref, lo, hi, m) != "mismatch", (name, uu)
+    # position-only: budget = N_init + N_k leaves no ranked rows, whatever the importance says
+    imp = torch.rand((H, stride), device=u.DEV)
+    kept = torch.full((H, stride), -1, dtype=torch.int32, device=u.DEV)
+    b_pos = np.array([n_init + Nk, n_init + Nk], np.int32)
+    len_out = hk.select(1, imp, np.full(H, T, np.int32), np.array([1, 1], np.uint8), b_pos, n_init, Nk, kept)
+    torch.cuda.synchronize()
+    want = np.concatenate([np.arange(n_init), np.arange(L, T)])
+    for uu in range(H):
+        assert np.array_equal(kept.cpu().numpy()[uu, :len_out[uu]], want)
+        assert np.array_equal(ho.select(imp.cpu().numpy()[uu, :T].astype(np.float64), 1, n_init + Nk, n_init, Nk), want)
+    hk.close()
