@@ -21,13 +21,13 @@ def _tol(cfg):
     return 1e-4 if cfg.dtype == "f32" else 2e-2
 
 
-def run_free(cfg, layer, units, steps=None, types=None, attention=None):
+def run_free(cfg, layer, units, steps=None, types=None, attention=None, with_pos=True):
     """hack_step over the schedule on all units; oracle on `units`.  Returns statistics."""
     u = _u()
     hk = u.make_hack(cfg, attention=attention)
     types = wl.head_types(cfg, layer) if types is None else np.asarray(types, np.uint8)
     cap = np.minimum(np.tile(wl.head_budgets(cfg, layer), cfg.batch), cfg.T_K)
-    mc = hk.managed_cache(cap)
+    mc = hk.managed_cache(cap, with_pos=with_pos)
     n_steps = cfg.n_steps if steps is None else steps
     data = wl.gen_layer(cfg, layer, range(1, n_steps + 1))
     budgets = [wl.step_budgets(cfg, layer, k) for k in range(1, n_steps + 1)]
@@ -46,7 +46,8 @@ def run_free(cfg, layer, units, steps=None, types=None, attention=None):
         torch.cuda.synchronize()
         off, ln = mc.view()
         assert np.array_equal(ln, plan[k - 1][2])                 # lengths are host-planned
-        got, kept_h, pos_h = u.from_dev(out), kept.cpu().numpy(), mc.pos.cpu().numpy()
+        got, kept_h = u.from_dev(out), kept.cpu().numpy()
+        pos_h = mc.pos.cpu().numpy() if with_pos else None
         for uu in units:
             if uu in diverged:
                 continue
@@ -63,7 +64,8 @@ def run_free(cfg, layer, units, steps=None, types=None, attention=None):
                 if verdict == "excused":
                     diverged.add(uu)          # its later steps see a different (equally valid) cache
                     continue
-            assert np.array_equal(pos_h[off[uu]:off[uu] + ln[uu]], r["pos"]), (k, uu)
+            if with_pos:
+                assert np.array_equal(pos_h[off[uu]:off[uu] + ln[uu]], r["pos"]), (k, uu)
             err = np.abs(got[b, h] - r["O"]).max()
             stats["max_err"] = max(stats["max_err"], float(err))
             assert err < _tol(cfg), (k, uu, err)
@@ -143,6 +145,15 @@ def test_schedule_with_either_attention_kernel_forced(attention):
     cfg = wl.get_config(4, keep=0.5, ctx_frac=0.25, batch=1)
     stats = run_free(cfg, 2, [0, 3, 5, 11], steps=11, attention=attention)
     assert stats["mismatch"] == 0 and stats["compress_events"] > 0
+
+
+def test_schedule_on_a_cache_without_position_ids():
+    """The token-id array of the managed cache is optional: appends (fused into the attention
+    launch or separate) and gathers must leave it alone when it is absent."""
+    cfg = wl.get_config(1, batch=1)
+    for attention in (None, "tile128"):
+        stats = run_free(cfg, 2, list(range(1, cfg.n_units, 6)), attention=attention, with_pos=False)
+        assert stats["mismatch"] == 0 and stats["compress_events"] > 0
 
 
 def test_cfg4_ragged_budgets_small_batch():
