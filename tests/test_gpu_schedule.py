@@ -240,17 +240,19 @@ def test_step_capacity_and_argument_errors():
     hk.close()
 
 
-@pytest.mark.parametrize("attention", [None, "tile128"])
-def test_graph_replays_reproduce_the_eager_schedule(attention):
+@pytest.mark.parametrize("cfg_id,batch,attention", [(1, 2, None), (1, 2, "tile128"), (2, None, None)])
+def test_graph_replays_reproduce_the_eager_schedule(cfg_id, batch, attention):
     """The whole schedule captured in a HIP graph (as bench.py launches it) is
     replayed several times, with eager work and synchronisations in between;
     every replay must reproduce the eager outputs, kept indices and final cache
     bit for bit (the kernels' workspaces have to come back clean every time).
     At this size the library's own choice sends every step to the key-split
     attention kernel with the append fused in; the second case captures the
-    128-query kernel and the separate append launches instead."""
+    128-query kernel and the separate append launches instead; the third is the
+    benchmark workload at full size, exactly as bench.py launches it (its eager
+    outputs are checked against the oracle by the full-size schedule tests)."""
     u = _u()
-    cfg = wl.get_config(1, batch=2)
+    cfg = wl.get_config(cfg_id, batch=batch)
     layer = 0
     hk = u.make_hack(cfg, attention=attention)
     types = wl.head_types(cfg, layer)
