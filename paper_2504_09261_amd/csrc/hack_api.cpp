@@ -43,8 +43,9 @@ struct hack_ctx {
   float* importance = nullptr;   // [max_units, ws_stride]
   int32_t* kept = nullptr;       // [max_units, ws_stride]
   double* stats = nullptr;       // fp32 path: [max_units, max_chunks, 32, 2] softmax partials
-  double* rowstat = nullptr;     // bf16 path: [max_units, 32] softmax normalisers, zero between launches
-  unsigned* counters = nullptr;  // bf16 path: [max_units, 2] arrival / reader counters, zero between launches
+  unsigned long long* rowstat = nullptr;  // bf16 path: [max_units, score_groups, 32] row-sum exchange slots, all-ones between launches
+  int score_groups = 0;          // work-groups a unit of max_cache_len keys is scored by
+  unsigned* counters = nullptr;  // bf16 path: [max_units, 2] reader counters, zero between launches
   float* hv_stats = nullptr;     // head variance: [max_units, max_queries, 2] softmax statistics of every query
   int* fault = nullptr;          // pinned, device-visible int[2]: [0] a score wave's bounded wait gave up (fatal),
                                  // [1] a logit exceeded the range the bf16 score kernel supports
@@ -292,7 +293,7 @@ void run_score(hack_ctx* ctx, hipStream_t s, const UnitDesc* ddev, const int32_t
   }
   for (size_t g = 0; g + 1 < group_begin.size(); ++g)
     launch_score_fused(s, ctx->cfg.head_dim, items_dev + group_begin[g], group_begin[g + 1] - group_begin[g], q,
-                       rows_dev, n_obs, N_k, scale, k_cache, k_new, ctx->rowstat, ctx->counters, importance,
+                       rows_dev, n_obs, N_k, scale, k_cache, k_new, ctx->rowstat, ctx->score_groups, ctx->counters, importance,
                        imp_stride, ctx->fault, kScoreSpinLimit);
 }
 
@@ -345,14 +346,16 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->importance, n_ws * sizeof(float));
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->kept, n_ws * sizeof(int32_t));
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->stats, (size_t)cfg->max_units * ctx->max_chunks * kMaxObs * 2 * sizeof(double));
-  if (e == hipSuccess) e = hipMalloc((void**)&ctx->rowstat, (size_t)cfg->max_units * kMaxObs * 2 * sizeof(double));
+  ctx->score_groups = ((cfg->max_cache_len + score_item_keys(HACK_BF16) - 1) / score_item_keys(HACK_BF16) + 3) / 4;
+  const size_t n_slots = (size_t)cfg->max_units * ctx->score_groups * kMaxObs;
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->rowstat, n_slots * sizeof(unsigned long long));
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, (size_t)cfg->max_units * 2 * sizeof(unsigned));
   if (e == hipSuccess) e = hipMemset(ctx->counters, 0, (size_t)cfg->max_units * 2 * sizeof(unsigned));
   if (e == hipSuccess && cfg->dtype == HACK_BF16)
     e = hipMalloc((void**)&ctx->hv_stats, (size_t)cfg->max_units * cfg->max_queries * 2 * sizeof(float));
   if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->fault, 2 * sizeof(int), hipHostMallocDefault);
   if (e == hipSuccess) ctx->fault[0] = ctx->fault[1] = 0;
-  if (e == hipSuccess) e = hipMemset(ctx->rowstat, 0, (size_t)cfg->max_units * kMaxObs * 2 * sizeof(double));
+  if (e == hipSuccess) e = hipMemset(ctx->rowstat, 0xFF, n_slots * sizeof(unsigned long long));   // every slot empty
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->arena_dev, kArenaBytes);
   if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->arena_host, kArenaBytes, hipHostMallocDefault);
@@ -361,7 +364,7 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
     // hold at most as many items as the device keeps resident at once
     ctx->score_capacity = score_fused_capacity(cfg->head_dim);
     const int per_unit = (cfg->max_cache_len + score_item_keys(cfg->dtype) - 1) / score_item_keys(cfg->dtype) + 3;
-    if (ctx->score_capacity < per_unit) e = hipErrorInvalidConfiguration;
+    if (ctx->score_capacity < per_unit || ctx->score_groups > score_max_groups()) e = hipErrorInvalidConfiguration;
   }
   if (e != hipSuccess) {
     hack_destroy(ctx);

@@ -59,10 +59,12 @@ void launch_move(hipStream_t s, int elem_bytes, int head_dim, const UnitDesc* de
 // consecutive entries, which must belong to one unit).  All items of a unit
 // must be in the same launch and n_items must not exceed
 // score_fused_capacity() (the waves the device holds at once: the kernel waits
-// inside a launch for a unit's items).  rowsum is a workspace of 32 doubles and
-// counters of 2 uint32 per `pos`, all zero on entry and left zero; q_rows DEVICE
-// int32[32]; fault (host-visible int[2]): [0] is set if a wait gave up after
-// spin_limit polls, [1] if a logit exceeded the range of the parked format.
+// inside a launch for a unit's items).  slots is a workspace of slot_groups * 32
+// 64-bit words per `pos` (slot_groups >= the work-groups of any unit), every word
+// all-ones on entry and left all-ones; counters 2 uint32 per `pos`, zero on entry
+// and left zero; q_rows DEVICE int32[32]; fault (host-visible int[2]): [0] is set
+// if a wait gave up after spin_limit polls, [1] if a logit exceeded the range of
+// the parked format.
 struct alignas(16) ScoreItem {
   int64_t in_off;    // first row of the unit's cached keys
   int32_t unit;      // u = b*H + h (rows of q/k_new start at u*N_k)
@@ -74,11 +76,12 @@ struct alignas(16) ScoreItem {
 };
 static_assert(sizeof(ScoreItem) == 32, "ScoreItem must stay 32 bytes");
 int score_item_keys(int dtype);
+int score_max_groups();   // work-groups per unit the fused kernel's exchange supports
 int score_fused_capacity(int head_dim);
 void launch_score_fused(hipStream_t s, int head_dim, const ScoreItem* items, int n_items, const void* q,
                         const int32_t* q_rows, int n_obs, int N_k, float scale, const void* k_cache,
-                        const void* k_new, double* rowsum, unsigned* counters, float* importance,
-                        int64_t imp_stride, int* fault, int spin_limit);
+                        const void* k_new, unsigned long long* slots, int slot_groups, unsigned* counters,
+                        float* importance, int64_t imp_stride, int* fault, int spin_limit);
 // fp32: two passes over (chunk of 256 keys, listed unit); list[n_list] indexes
 // descs; stats is a workspace of n_list * ceil(max_t_in / 256) * 64 doubles.
 void launch_score_generic(hipStream_t s, int head_dim, const UnitDesc* descs, const int32_t* list, int n_list,

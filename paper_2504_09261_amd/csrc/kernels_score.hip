@@ -10,9 +10,9 @@
 // bf16 (score_fused): one launch that reads K once.  One
 // v_mfma_f32_32x32x16_bf16 column block holds all 32 observation rows; a wave
 // takes 128 keys as four 32-key tiles copied HBM -> LDS asynchronously, parks
-// the logits in registers, contributes to the unit's l_i through fp64 atomics,
-// waits (bounded) for the other work-groups of the unit and then writes
-// importance_j = sum_i 2^t_ij / l_i from the parked logits.
+// the logits in registers, publishes its work-group's row sums in a per-unit
+// exchange area, collects (bounded wait) those of the unit's other work-groups
+// and then writes importance_j = sum_i 2^t_ij / l_i from the parked logits.
 // fp32 (score_generic): two streaming passes over (unit, chunk of 256 keys),
 // plain fp64 FMA dot products, one key per lane:
 //   pass 1  per chunk and observation row: max logit and sum of exp(logit - max)
@@ -210,6 +210,8 @@ template <int N> __device__ __forceinline__ void score_wait_vm() {
 // (354 nats), far outside anything a float32 importance can resolve.
 constexpr double kFixOne = 4194304.0;  // 2^22
 constexpr int kFixLimit = 511 << 22;
+constexpr int kMaxGroups = 64;                 // work-groups per unit the exchange supports (4 * 128 keys each)
+constexpr unsigned long long kEmpty = ~0ull;   // exchange slot not published yet (a NaN pattern no row sum can have)
 __device__ __forceinline__ int fix_from(double t_scaled) {  // t_scaled = t * 2^22
   t_scaled = fmin(fmax(t_scaled, -511.0 * kFixOne), 511.0 * kFixOne);
   return __double2int_rn(t_scaled);
@@ -241,25 +243,32 @@ __device__ __forceinline__ double half_sum_f64(double v) {
 // One launch, K read once.  Every wave
 //   A. forms the logits t_ij (log2 units) of its item, 32 observation rows x up
 //      to kItemKeys keys, and parks them in registers as fixed point;
-//   B. adds the row sums of p_ij = 2^t_ij (doubles: the fp64 exponent range makes
-//      a running maximum unnecessary) to the unit's 32 softmax normalisers l_i
-//      with device-scope fp64 atomics and bumps the unit's arrival counter;
-//   C. waits until all items of the unit have arrived, reads the l_i back and
-//      writes importance_j = sum_i p_ij / l_i for its keys.
-// The wait in C needs every item of a unit to be resident at the same time: the
-// host never launches more waves than the device holds at once (occupancy x
-// compute units), so all of them run concurrently and each arrives without
-// depending on anyone else.  The wait is bounded all the same: a wave that runs
-// out of polls raises fault[0] (host-visible) and leaves without writing, and the
-// host refuses further work on the context.  fault[1] reports clamped logits.  The wave that is last to read a
-// unit's sums zeroes sums and counters again for the next launch.
+//   B. forms the row sums of p_ij = 2^t_ij (doubles: the fp64 exponent range makes
+//      a running maximum unnecessary); the four waves of a work-group (always items
+//      of one unit) add theirs and publish the 32 sums in the work-group's own slot
+//      of the unit's exchange area with device-coherent stores;
+//   C. collects the slots of all work-groups of the unit (device-coherent loads,
+//      repeated until a slot no longer holds the "empty" bit pattern), adds them in
+//      a fixed order, so every work-group gets the same normalisers l_i bit for bit,
+//      and writes importance_j = sum_i p_ij / l_i for its keys.
+// A slot value carries its own validity (a sum of powers of two is never the
+// all-ones NaN pattern), so no ordering between different addresses is needed:
+// one store and, normally, one or two rounds of loads replace atomic round trips.
+// The wait in C needs every work-group of a unit to be resident at the same time:
+// the host never launches more waves than the device holds at once (occupancy x
+// compute units), so all of them run concurrently and each publishes without
+// depending on anyone else.  The wait is bounded all the same: a thread that runs
+// out of polls raises fault[0] (host-visible), the work-group leaves without
+// writing, and the host refuses further work on the context.  fault[1] reports
+// clamped logits.  Each work-group draws a ticket after it has read; the one that
+// draws the unit's last ticket marks the unit's slots empty again for the next launch.
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void score_fused(
     const ScoreItem* __restrict__ items, int n_items, const __bf16* __restrict__ q,
     const int32_t* __restrict__ q_rows, int n_obs, int N_k, float scale,
     const __bf16* __restrict__ k_cache, const __bf16* __restrict__ k_new,
-    double* __restrict__ rowsum, unsigned* __restrict__ counters, float* __restrict__ importance,
-    int64_t imp_stride, int* __restrict__ fault, int spin_limit) {
+    unsigned long long* __restrict__ slots, int slot_groups, unsigned* __restrict__ counters,
+    float* __restrict__ importance, int64_t imp_stride, int* __restrict__ fault, int spin_limit) {
   constexpr int KK = D / 16;            // MFMA steps over the head dimension
   constexpr int CPR = D / 8;            // 16-byte chunks per row
   constexpr int RPI = 64 / CPR;         // rows per wave-wide copy instruction
@@ -277,8 +286,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
 
   __shared__ __attribute__((aligned(1024))) __bf16 tiles[4][2][TILE];
   const unsigned lds0 = (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)&tiles[w][0][0];
-  double* sum_unit = rowsum + (int64_t)it.pos * kMaxObs;
-  unsigned* cnt = counters + 2 * it.pos;   // [0] arrivals, [1] readers done
+  // exchange area of the unit: [work-group of the unit][observation row], kEmpty = not published yet
+  unsigned long long* unit_slots = slots + (int64_t)it.pos * slot_groups * kMaxObs;
+  const int group = it.chunk >> 2;         // this work-group's index inside the unit (4 items per work-group)
+  unsigned* cnt = counters + 2 * it.pos;   // [1] work-groups that have read the unit's slots
 
   // copy of tile t (keys key0 + 32t ..) into buffer t & 1.  A tile that lies
   // wholly inside the cached rows or wholly inside the new rows (the common
@@ -385,12 +396,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
     }
   }
 
-  // ---- B: row sums -> unit normalisers, then announce arrival ---------------
-  // The four waves of a work-group hold items of the same unit.  Each wave's
-  // tile buffers are free by now, so they carry the exchange: every wave leaves
-  // its 32 row sums there, wave 0 adds the four and sends one atomic per row.
-  // The atomics return their old value: once it is back the add has been
-  // performed, so the arrival that follows is ordered after the contributions.
+  // ---- B: row sums of the work-group -> its slot ------------------------------
+  // Each wave's tile buffers are free by now, so they carry the exchange inside
+  // the work-group: every wave leaves its 32 row sums there, wave 0 adds the four
+  // and publishes one value per row.
   double* red = reinterpret_cast<double*>(&tiles[w][0][0]);
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
@@ -402,46 +411,64 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
     if (col == 0) red[c_row(r, half)] = l;
   }
   __syncthreads();
-  double* inv_s = reinterpret_cast<double*>(&tiles[0][0][0]) + 64;  // in wave 0's buffer, after its sums
+  if (w == 0 && lane < kMaxObs) {
+    double tot = 0.0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) tot += reinterpret_cast<const double*>(&tiles[k][0][0])[lane];
+    __hip_atomic_store(&unit_slots[group * kMaxObs + lane], (unsigned long long)__double_as_longlong(tot),
+                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // ---- C: collect the unit's slots ---------------------------------------------
+  // thread (sub, row) = (tid / 32, tid % 32) takes work-groups sub, sub + 8, ... of row `row`
+  double* part8 = reinterpret_cast<double*>(&tiles[1][0][0]) + 64;   // [8][32] partial sums, behind wave 1's row sums
+  double* inv_s = reinterpret_cast<double*>(&tiles[0][0][0]) + 64;   // [32], behind wave 0's row sums
   int* ok_s = reinterpret_cast<int*>(inv_s + kMaxObs);
+  if (tid == 0) *ok_s = 1;
+  __syncthreads();
+  {
+    const int row = tid & 31, sub = tid >> 5;
+    // up to kMaxGroups / 8 slots per thread: all loads are issued first, then each is
+    // repeated until it is valid (work-groups past the end count as +0.0)
+    unsigned long long bits[kMaxGroups / 8];
+#pragma unroll
+    for (int k = 0; k < kMaxGroups / 8; ++k) {
+      const int g2 = sub + 8 * k;
+      bits[k] = (g2 < it.n_groups) ? __hip_atomic_load(&unit_slots[g2 * kMaxObs + row], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                   : 0ull;
+    }
+    double acc = 0.0;
+    bool ok = true;
+#pragma unroll
+    for (int k = 0; k < kMaxGroups / 8; ++k) {
+      int polls = 0;
+      while (bits[k] == kEmpty) {
+        if (++polls > spin_limit) { ok = false; break; }
+        __builtin_amdgcn_s_sleep(8);
+        bits[k] = __hip_atomic_load(&unit_slots[(sub + 8 * k) * kMaxObs + row], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      acc += __longlong_as_double((long long)bits[k]);
+    }
+    part8[sub * kMaxObs + row] = acc;
+    if (!ok) *ok_s = 0;
+  }
+  __syncthreads();
+  if (*ok_s == 0) {
+    if (tid == 0) __hip_atomic_store(fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    return;
+  }
   unsigned ticket = 0;
   if (w == 0) {
     if (lane < kMaxObs) {
-      double tot = 0.0;
+      double l = 0.0;
 #pragma unroll
-      for (int k = 0; k < 4; ++k) tot += reinterpret_cast<const double*>(&tiles[k][0][0])[lane];
-      const double old = atomicAdd(&sum_unit[lane], tot);
-      asm volatile("" ::"v"(old));
+      for (int k = 0; k < 8; ++k) l += part8[k * kMaxObs + lane];   // fixed order: the same bits in every work-group
+      inv_s[lane] = (lane < n_obs) ? 1.0 / l : 0.0;
     }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    // ---- C: wait for the unit, read the normalisers -------------------------
-    int ok = 1;
-    if (lane == 0) {
-      unsigned seen = atomicAdd(&cnt[0], 1u) + 1u;
-      int polls = 0;
-      while (seen < (unsigned)it.n_groups) {
-        if (++polls > spin_limit) { ok = 0; break; }
-        __builtin_amdgcn_s_sleep(16);
-        seen = atomicAdd(&cnt[0], 0u);   // read-modify-write: always served at the coherence point
-      }
-    }
-    ok = __builtin_amdgcn_readfirstlane(ok);
-    if (ok) {
-      if (lane < kMaxObs) {
-        const double l = atomicAdd(&sum_unit[lane], 0.0);
-        inv_s[lane] = (lane < n_obs) ? 1.0 / l : 0.0;
-      }
-      // the read is back before the ticket is drawn: whoever draws the last
-      // ticket may clear the sums without racing any reader
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      if (lane == 0) ticket = atomicAdd(&cnt[1], 1u);
-    } else if (lane == 0) {
-      __hip_atomic_store(fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    }
-    if (lane == 0) *ok_s = ok;
+    // every slot this work-group needed has been read (the values were used above):
+    // whoever draws the last ticket may mark the slots empty without racing a reader
+    if (lane == 0) ticket = atomicAdd(&cnt[1], 1u);
   }
   __syncthreads();
-  if (*ok_s == 0) return;
   double inv_r[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) inv_r[r] = inv_s[c_row(r, half)];
@@ -458,11 +485,12 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
     }
   }
   if (w == 0) {
-    // the wave that drew a unit's last ticket leaves sums and counters zeroed for the next launch
+    // the work-group that drew a unit's last ticket leaves slots and counter as the next launch expects them
     ticket = __builtin_amdgcn_readfirstlane(ticket);
     if ((int)ticket == it.n_groups - 1) {
-      if (lane < kMaxObs) sum_unit[lane] = 0.0;
-      if (lane < 2) cnt[lane] = 0;
+      for (int e = lane; e < it.n_groups * kMaxObs; e += 64)
+        __hip_atomic_store(&unit_slots[e], kEmpty, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (lane == 0) cnt[1] = 0;
     }
   }
 }
@@ -483,6 +511,7 @@ void launch_generic(hipStream_t s, dim3 grid, const UnitDesc* descs, const int32
 }  // namespace
 
 int score_item_keys(int dtype) { return dtype == 1 ? kScoreChunk : kItemKeys; }
+int score_max_groups() { return kMaxGroups; }
 
 int score_fused_capacity(int head_dim) {
   int dev = 0, cus = 0, blocks = 0;
@@ -497,19 +526,19 @@ int score_fused_capacity(int head_dim) {
 
 void launch_score_fused(hipStream_t s, int head_dim, const ScoreItem* items, int n_items, const void* q,
                         const int32_t* q_rows, int n_obs, int N_k, float scale, const void* k_cache,
-                        const void* k_new, double* rowsum, unsigned* counters, float* importance,
-                        int64_t imp_stride, int* fault, int spin_limit) {
+                        const void* k_new, unsigned long long* slots, int slot_groups, unsigned* counters,
+                        float* importance, int64_t imp_stride, int* fault, int spin_limit) {
   if (n_items <= 0) return;
   typedef __bf16 T;
   dim3 grid((n_items + 3) / 4);
   if (head_dim == 64)
     hipLaunchKernelGGL(score_fused<64>, grid, dim3(kThreads), 0, s, items, n_items, (const T*)q, q_rows, n_obs,
-                       N_k, scale, (const T*)k_cache, (const T*)k_new, rowsum, counters, importance, imp_stride,
-                       fault, spin_limit);
+                       N_k, scale, (const T*)k_cache, (const T*)k_new, slots, slot_groups, counters, importance,
+                       imp_stride, fault, spin_limit);
   else
     hipLaunchKernelGGL(score_fused<128>, grid, dim3(kThreads), 0, s, items, n_items, (const T*)q, q_rows, n_obs,
-                       N_k, scale, (const T*)k_cache, (const T*)k_new, rowsum, counters, importance, imp_stride,
-                       fault, spin_limit);
+                       N_k, scale, (const T*)k_cache, (const T*)k_new, slots, slot_groups, counters, importance,
+                       imp_stride, fault, spin_limit);
 }
 
 void launch_score_generic(hipStream_t s, int head_dim, const UnitDesc* descs, const int32_t* list, int n_list,
