@@ -45,6 +45,7 @@ struct hack_ctx {
   double* stats = nullptr;       // fp32 path: [max_units, max_chunks, 32, 2] softmax partials
   unsigned long long* rowstat = nullptr;  // bf16 path: [max_units, score_groups, 32] row-sum exchange slots, all-ones between launches
   int score_groups = 0;          // work-groups a unit of max_cache_len keys is scored by
+  int spin_limit = 0;            // polls after which a score work-group gives up its wait for the unit's other work-groups
   unsigned* counters = nullptr;  // bf16 path: [max_units, 2] reader counters, zero between launches
   float* hv_stats = nullptr;     // head variance: [max_units, max_queries, 2] softmax statistics of every query
   int* fault = nullptr;          // pinned, device-visible int[2]: [0] a score wave's bounded wait gave up (fatal),
@@ -294,7 +295,7 @@ void run_score(hack_ctx* ctx, hipStream_t s, const UnitDesc* ddev, const int32_t
   for (size_t g = 0; g + 1 < group_begin.size(); ++g)
     launch_score_fused(s, ctx->cfg.head_dim, items_dev + group_begin[g], group_begin[g + 1] - group_begin[g], q,
                        rows_dev, n_obs, N_k, scale, k_cache, k_new, ctx->rowstat, ctx->score_groups, ctx->counters, importance,
-                       imp_stride, ctx->fault, kScoreSpinLimit);
+                       imp_stride, ctx->fault, ctx->spin_limit);
 }
 
 void fill_q_rows(const int32_t* q_idx, int n_obs, int N_k, int32_t* rows) {
@@ -340,6 +341,9 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   ctx->ws_stride = round_up(cfg->max_cache_len, 64);
   ctx->max_chunks = (cfg->max_cache_len + kScoreChunk - 1) / kScoreChunk;
   ctx->split_max_items = split_max_items_default(cfg->head_dim);
+  ctx->spin_limit = kScoreSpinLimit;
+  // test hook: a tiny limit makes the score kernel's bounded wait give up (every work-group still exits normally)
+  if (const char* v = std::getenv("HACK_SCORE_SPIN_LIMIT")) ctx->spin_limit = std::max(0, std::atoi(v));
   if (const char* v = std::getenv("HACK_ATTN_SPLIT_ITEMS")) ctx->split_max_items = std::atoi(v);   // tuning / test override
   hipError_t e = hipSetDevice(cfg->device);
   const size_t n_ws = (size_t)cfg->max_units * ctx->ws_stride;

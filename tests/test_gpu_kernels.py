@@ -386,3 +386,45 @@ def test_attention_variant_query_matches_the_documented_rule():
     with pytest.raises(HackError):
         hk.attn_variant(0, 4)
     hk.close()
+
+
+def test_score_bounded_wait_gives_up_and_is_reported(monkeypatch):
+    """The in-kernel wait of the bf16 score kernel is bounded.  With the poll limit forced to zero
+    from the host, a work-group that finds another one's row sums not yet published gives up at
+    once: every work-group still exits normally, the condition is raised in the host-visible
+    flag, hack_check reports it and the context refuses further work."""
+    u = _u()
+    monkeypatch.setenv("HACK_SCORE_SPIN_LIMIT", "0")
+    rng = np.random.default_rng(9)
+    H, d, dtype, Nk = 4, 128, "bf16", 64
+    hk = u.make_hack(heads=H, head_dim=d, dtype=dtype, max_units=H, max_cache_len=8192, max_queries=Nk)
+    monkeypatch.delenv("HACK_SCORE_SPIN_LIMIT")
+    rows = [(u.rand_values(rng, (8000, d), dtype), u.rand_values(rng, (8, d), dtype)[:0]) for _ in range(H)]
+    K = np.zeros((H * 8000, d), np.float32)
+    for i, (k, _) in enumerate(rows):
+        K[i * 8000:(i + 1) * 8000] = k
+    Kd = u.to_dev(K, dtype)
+    cin = Cache(Kd, Kd, np.arange(H, dtype=np.int64) * 8000, np.full(H, 8000, np.int32))
+    q = u.to_dev(u.rand_values(rng, (1, H, Nk, d), dtype), dtype)
+    imp = torch.zeros((H, 8192), device=u.DEV)
+    gave_up = False
+    for _ in range(5):                      # 16 work-groups per unit: the first to arrive practically always finds an empty slot
+        try:
+            hk.score(q, cin, 0.05, imp)
+            torch.cuda.synchronize()
+            hk.check()
+        except HackError as e:
+            assert e.status == -4
+            gave_up = True
+            break
+    assert gave_up
+    with pytest.raises(HackError):          # the context stays refused
+        hk.score(q, cin, 0.05, imp)
+    hk.close()
+    # a fresh context with the normal limit works on the same inputs
+    hk = u.make_hack(heads=H, head_dim=d, dtype=dtype, max_units=H, max_cache_len=8192, max_queries=Nk)
+    hk.score(q, cin, 0.05, imp)
+    torch.cuda.synchronize()
+    hk.check()
+    assert abs(float(imp[0].sum()) - 32.0) < 1e-3
+    hk.close()
