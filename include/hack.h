@@ -117,7 +117,8 @@ hack_status hack_check(hack_ctx* ctx);
  * |scale * q.k| stays below ~40, and within 2.5e-8 * max|scale * q.k| beyond.
  * Logits are supported up to |scale * q.k| <= 354 (far beyond what a float32
  * importance can resolve); larger ones are clamped and reported by hack_check /
- * the next call.
+ * the next call.  Results are reproducible bit for bit from call to call: every
+ * sum is formed in a fixed order (no floating-point atomics).
  * Errors: HACK_EINVAL (NULL/misaligned pointers, n_obs out of range, a q_idx
  * outside [0, N_k), offsets outside the cache), HACK_ECAPACITY (B*H, N_k or a
  * T_in above the context's limits, imp_stride < max T_in). */
