@@ -50,7 +50,8 @@ struct hack_ctx {
   float* hv_stats = nullptr;     // head variance: [max_units, max_queries, 2] softmax statistics of every query
   int* fault = nullptr;          // pinned, device-visible int[2]: [0] a score wave's bounded wait gave up (fatal),
                                  // [1] a logit exceeded the range the bf16 score kernel supports
-  int score_capacity = 0;        // bf16 path: score items one launch may hold (resident waves)
+  int score_capacity = 0;        // bf16 path: score items one launch may hold (resident waves), default item size
+  int score_capacity_large = 0;  // the same for the larger item size
   int split_max_items = 0;       // launches with at most this many 32-query attention items use the key-split kernel
   int64_t ws_stride = 0;
   int max_chunks = 0;
@@ -282,9 +283,28 @@ void build_score_items(const std::vector<UnitDesc>& descs, const std::vector<int
   group_begin->push_back((int)items->size());
 }
 
+// bf16: builds the score items of the listed units.  The default item size is used unless the items would
+// not fit one launch and the larger size gets by with fewer launches (every launch pays the kernel's
+// latency chain again).  Returns the item size chosen.
+int plan_score_items(const hack_ctx* ctx, const std::vector<UnitDesc>& descs, const std::vector<int32_t>& list,
+                     std::vector<ScoreItem>* items, std::vector<int>* group_begin) {
+  const int small = score_item_keys(HACK_BF16), large = score_item_keys_large();
+  build_score_items(descs, list, small, ctx->score_capacity, items, group_begin);
+  if (group_begin->size() <= 2 || ctx->score_capacity_large <= 0) return small;
+  std::vector<ScoreItem> items_l;
+  std::vector<int> groups_l;
+  build_score_items(descs, list, large, ctx->score_capacity_large, &items_l, &groups_l);
+  if (groups_l.size() < group_begin->size()) {
+    items->swap(items_l);
+    group_begin->swap(groups_l);
+    return large;
+  }
+  return small;
+}
+
 // Scores the listed units of a table that is already on the device.
 void run_score(hack_ctx* ctx, hipStream_t s, const UnitDesc* ddev, const int32_t* list_dev, int n_list, int max_t,
-               const ScoreItem* items_dev, const std::vector<int>& group_begin, const void* q,
+               const ScoreItem* items_dev, int item_keys, const std::vector<int>& group_begin, const void* q,
                const int32_t* rows_dev, int n_obs, int N_k, float scale, const void* k_cache, const void* k_new,
                float* importance, int64_t imp_stride) {
   if (ctx->cfg.dtype == HACK_F32) {
@@ -293,7 +313,7 @@ void run_score(hack_ctx* ctx, hipStream_t s, const UnitDesc* ddev, const int32_t
     return;
   }
   for (size_t g = 0; g + 1 < group_begin.size(); ++g)
-    launch_score_fused(s, ctx->cfg.head_dim, items_dev + group_begin[g], group_begin[g + 1] - group_begin[g], q,
+    launch_score_fused(s, ctx->cfg.head_dim, item_keys, items_dev + group_begin[g], group_begin[g + 1] - group_begin[g], q,
                        rows_dev, n_obs, N_k, scale, k_cache, k_new, ctx->rowstat, ctx->score_groups, ctx->counters, importance,
                        imp_stride, ctx->fault, ctx->spin_limit);
 }
@@ -366,7 +386,8 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (e == hipSuccess && cfg->dtype == HACK_BF16) {
     // a unit's score items wait for each other inside one launch, so a launch may
     // hold at most as many items as the device keeps resident at once
-    ctx->score_capacity = score_fused_capacity(cfg->head_dim);
+    ctx->score_capacity = score_fused_capacity(cfg->head_dim, score_item_keys(HACK_BF16));
+    ctx->score_capacity_large = score_fused_capacity(cfg->head_dim, score_item_keys_large());
     const int per_unit = (cfg->max_cache_len + score_item_keys(cfg->dtype) - 1) / score_item_keys(cfg->dtype) + 3;
     if (ctx->score_capacity < per_unit || ctx->score_groups > score_max_groups()) e = hipErrorInvalidConfiguration;
   }
@@ -432,8 +453,8 @@ extern "C" hack_status hack_score(hack_ctx* ctx, int32_t B, int32_t N_k, const v
   fill_q_rows(q_idx, n_obs, N_k, rows);
   std::vector<ScoreItem> sitems;
   std::vector<int> groups;
-  if (ctx->cfg.dtype == HACK_BF16)
-    build_score_items(descs, list, score_item_keys(ctx->cfg.dtype), ctx->score_capacity, &sitems, &groups);
+  int item_keys = 0;
+  if (ctx->cfg.dtype == HACK_BF16) item_keys = plan_score_items(ctx, descs, list, &sitems, &groups);
   Table t;
   const size_t o_desc = t.add(descs.data(), descs.size());
   const size_t o_list = t.add(list.data(), list.size());
@@ -443,7 +464,7 @@ extern "C" hack_status hack_score(hack_ctx* ctx, int32_t B, int32_t N_k, const v
   hipStream_t s = static_cast<hipStream_t>(stream);
   if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
   run_score(ctx, s, (const UnitDesc*)(dev + o_desc), (const int32_t*)(dev + o_list), (int)list.size(), max_t,
-            (const ScoreItem*)(dev + o_sit), groups, q, (const int32_t*)(dev + o_rows), n_obs, N_k, scale, in->k, k_new,
+            (const ScoreItem*)(dev + o_sit), item_keys, groups, q, (const int32_t*)(dev + o_rows), n_obs, N_k, scale, in->k, k_new,
             importance, imp_stride);
   HIP_TRY(ctx, hipGetLastError());
   return HACK_OK;
@@ -739,8 +760,8 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
 
   std::vector<ScoreItem> sitems;
   std::vector<int> groups;
-  if (ctx->cfg.dtype == HACK_BF16)
-    build_score_items(descs, comp, score_item_keys(ctx->cfg.dtype), ctx->score_capacity, &sitems, &groups);
+  int item_keys = 0;
+  if (ctx->cfg.dtype == HACK_BF16) item_keys = plan_score_items(ctx, descs, comp, &sitems, &groups);
   Table t;
   const size_t o_desc = t.add(descs.data(), descs.size());
   const size_t o_comp = t.add(comp.data(), comp.size());
@@ -755,7 +776,7 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
 
   if (!comp.empty()) {
     run_score(ctx, s, ddev, (const int32_t*)(dev + o_comp), (int)comp.size(), max_t, (const ScoreItem*)(dev + o_sit),
-              groups, q, (const int32_t*)(dev + o_rows), n_obs, N_k, scale, cache->k, k_new, ctx->importance,
+              item_keys, groups, q, (const int32_t*)(dev + o_rows), n_obs, N_k, scale, cache->k, k_new, ctx->importance,
               ctx->ws_stride);
     launch_select(s, ddev, (const int32_t*)(dev + o_comp), (int)comp.size(), max_t, ctx->importance, ctx->ws_stride, kept,
                   kstride);

@@ -54,11 +54,11 @@ void launch_move(hipStream_t s, int elem_bytes, int head_dim, const UnitDesc* de
                  int N_k, int pos_new, const int32_t* kept_idx, int64_t idx_stride);
 
 // Subset-attention importance, bf16: one launch over `items`, a DEVICE array with
-// one entry per chunk of score_item_keys() keys of every scored unit, each unit
+// one entry per chunk of item_keys keys (score_item_keys() or score_item_keys_large()) of every scored unit, each unit
 // padded with empty chunks to a multiple of 4 entries (one work-group takes 4
 // consecutive entries, which must belong to one unit).  All items of a unit
 // must be in the same launch and n_items must not exceed
-// score_fused_capacity() (the waves the device holds at once: the kernel waits
+// score_fused_capacity(head_dim, item_keys) (the waves the device holds at once: the kernel waits
 // inside a launch for a unit's items).  slots is a workspace of slot_groups * 32
 // 64-bit words per `pos` (slot_groups >= the work-groups of any unit), every word
 // all-ones on entry and left all-ones; counters 2 uint32 per `pos`, zero on entry
@@ -77,8 +77,9 @@ struct alignas(16) ScoreItem {
 static_assert(sizeof(ScoreItem) == 32, "ScoreItem must stay 32 bytes");
 int score_item_keys(int dtype);
 int score_max_groups();   // work-groups per unit the fused kernel's exchange supports
-int score_fused_capacity(int head_dim);
-void launch_score_fused(hipStream_t s, int head_dim, const ScoreItem* items, int n_items, const void* q,
+int score_item_keys_large();   // bf16: the larger item size, used when the default would not fit one launch
+int score_fused_capacity(int head_dim, int item_keys);
+void launch_score_fused(hipStream_t s, int head_dim, int item_keys, const ScoreItem* items, int n_items, const void* q,
                         const int32_t* q_rows, int n_obs, int N_k, float scale, const void* k_cache,
                         const void* k_new, unsigned long long* slots, int slot_groups, unsigned* counters,
                         float* importance, int64_t imp_stride, int* fault, int spin_limit);

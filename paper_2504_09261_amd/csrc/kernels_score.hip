@@ -173,7 +173,7 @@ __global__ __launch_bounds__(kThreads) void score_generic(
 __device__ __forceinline__ int c_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
 // ---- wave-private tile pipeline -------------------------------------------
-// A work item is (unit, chunk of kItemKeys keys) and belongs to ONE wave: the
+// A work item is (unit, chunk of 32 TILES keys, TILES = 4 or 8) and belongs to ONE wave: the
 // wave copies its 32-key tiles HBM -> LDS with global_load_lds (16 B per lane,
 // whole rows, fully coalesced), double-buffered in a private LDS region, and
 // reads MFMA operands back with ds_read_b128 (XOR-swizzled chunks, conflict
@@ -181,8 +181,8 @@ __device__ __forceinline__ int c_row(int r, int half) { return 8 * (r >> 2) + 4 
 // wait on their own copies (hand-placed s_waitcnt vmcnt), so they drift freely and
 // keep HBM busy.  Reading K fragments straight from HBM in operand layout would touch
 // 32 rows x 32 bytes per instruction and re-fetch every cache line several times.
-constexpr int kItemKeys = 128;                 // keys per wave item
-constexpr int kItemTiles = kItemKeys / 32;
+constexpr int kItemKeys = 128;                 // keys per wave item (TILES = 4), the default
+constexpr int kItemKeysLarge = 256;            // TILES = 8: halves the items when a launch would not hold them all
 
 template <int D> __device__ __forceinline__ int score_swz(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
 
@@ -242,7 +242,7 @@ __device__ __forceinline__ double half_sum_f64(double v) {
 
 // One launch, K read once.  Every wave
 //   A. forms the logits t_ij (log2 units) of its item, 32 observation rows x up
-//      to kItemKeys keys, and parks them in registers as fixed point;
+//      to 32 TILES keys, and parks them in registers as fixed point;
 //   B. forms the row sums of p_ij = 2^t_ij (doubles: the fp64 exponent range makes
 //      a running maximum unnecessary); the four waves of a work-group (always items
 //      of one unit) add theirs and publish the 32 sums in the work-group's own slot
@@ -262,7 +262,7 @@ __device__ __forceinline__ double half_sum_f64(double v) {
 // writing, and the host refuses further work on the context.  fault[1] reports
 // clamped logits.  Each work-group draws a ticket after it has read; the one that
 // draws the unit's last ticket marks the unit's slots empty again for the next launch.
-template <int D>
+template <int D, int TILES>
 __global__ __launch_bounds__(kThreads, 2) void score_fused(
     const ScoreItem* __restrict__ items, int n_items, const __bf16* __restrict__ q,
     const int32_t* __restrict__ q_rows, int n_obs, int N_k, float scale,
@@ -280,7 +280,8 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
   const int item = blockIdx.x * 4 + w;  // the host pads every unit to whole work-groups
   const ScoreItem it = items[item];
   const int T_in = it.t_in;
-  const int key0 = it.chunk * kItemKeys;
+  constexpr int kItemTiles = TILES;
+  const int key0 = it.chunk * (32 * TILES);
   const int n_tiles = max(0, min(kItemTiles, (T_in - key0 + 31) / 32));  // 0: padding item
   const int col = lane & 31, half = lane >> 5;
 
@@ -511,34 +512,42 @@ void launch_generic(hipStream_t s, dim3 grid, const UnitDesc* descs, const int32
 }  // namespace
 
 int score_item_keys(int dtype) { return dtype == 1 ? kScoreChunk : kItemKeys; }
+int score_item_keys_large() { return kItemKeysLarge; }
 int score_max_groups() { return kMaxGroups; }
 
-int score_fused_capacity(int head_dim) {
+int score_fused_capacity(int head_dim, int item_keys) {
   int dev = 0, cus = 0, blocks = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-  const hipError_t e = head_dim == 64
-      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<64>, kThreads, 0)
-      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<128>, kThreads, 0);
+  hipError_t e;
+  if (item_keys == kItemKeysLarge)
+    e = head_dim == 64 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<64, 8>, kThreads, 0)
+                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<128, 8>, kThreads, 0);
+  else
+    e = head_dim == 64 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<64, 4>, kThreads, 0)
+                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<128, 4>, kThreads, 0);
   if (e != hipSuccess) return 0;
   return blocks * cus * (kThreads / 64);
 }
 
-void launch_score_fused(hipStream_t s, int head_dim, const ScoreItem* items, int n_items, const void* q,
+void launch_score_fused(hipStream_t s, int head_dim, int item_keys, const ScoreItem* items, int n_items, const void* q,
                         const int32_t* q_rows, int n_obs, int N_k, float scale, const void* k_cache,
                         const void* k_new, unsigned long long* slots, int slot_groups, unsigned* counters,
                         float* importance, int64_t imp_stride, int* fault, int spin_limit) {
   if (n_items <= 0) return;
   typedef __bf16 T;
   dim3 grid((n_items + 3) / 4);
-  if (head_dim == 64)
-    hipLaunchKernelGGL(score_fused<64>, grid, dim3(kThreads), 0, s, items, n_items, (const T*)q, q_rows, n_obs,
-                       N_k, scale, (const T*)k_cache, (const T*)k_new, slots, slot_groups, counters, importance,
-                       imp_stride, fault, spin_limit);
-  else
-    hipLaunchKernelGGL(score_fused<128>, grid, dim3(kThreads), 0, s, items, n_items, (const T*)q, q_rows, n_obs,
-                       N_k, scale, (const T*)k_cache, (const T*)k_new, slots, slot_groups, counters, importance,
-                       imp_stride, fault, spin_limit);
+#define HACK_SCORE_ARGS grid, dim3(kThreads), 0, s, items, n_items, (const T*)q, q_rows, n_obs, N_k, scale, (const T*)k_cache, \
+                        (const T*)k_new, slots, slot_groups, counters, importance, imp_stride, fault, spin_limit
+  const bool large = item_keys == kItemKeysLarge;
+  if (head_dim == 64) {
+    if (large) hipLaunchKernelGGL((score_fused<64, 8>), HACK_SCORE_ARGS);
+    else hipLaunchKernelGGL((score_fused<64, 4>), HACK_SCORE_ARGS);
+  } else {
+    if (large) hipLaunchKernelGGL((score_fused<128, 8>), HACK_SCORE_ARGS);
+    else hipLaunchKernelGGL((score_fused<128, 4>), HACK_SCORE_ARGS);
+  }
+#undef HACK_SCORE_ARGS
 }
 
 void launch_score_generic(hipStream_t s, int head_dim, const UnitDesc* descs, const int32_t* list, int n_list,
