@@ -94,11 +94,36 @@ const char* hack_last_error(const hack_ctx* ctx);
  *                      |scale * q.k| > 354: its importance was formed with that
  *                      logit clamped and may differ from the definition.
  *                      Reported once, the context stays usable.
- *   HACK_EHIP          a score kernel gave up its bounded wait for the other
- *                      work-groups of a unit (the device did not keep the
- *                      launch resident): its output is incomplete and the
- *                      context must be destroyed. */
+ *   HACK_EHIP          a fused score launch gave up its bounded wait for the
+ *                      other work-groups of a unit (the device did not keep
+ *                      the launch resident as a whole, e.g. other work held
+ *                      compute units).  Importance, kept indices, caches and
+ *                      outputs produced by the calls since the last successful
+ *                      check are incomplete: reset the managed cache and issue
+ *                      those calls again.  Fused score launches queued after
+ *                      the failing one have not run at all (they find a flag
+ *                      in device memory and leave before reading anything).
+ *                      The call that reports this drains the device, re-arms
+ *                      the workspace and switches the context to
+ *                      HACK_SCORE_TWO_PASS; the context stays usable.  HIP
+ *                      graphs captured before keep their fused launches. */
 hack_status hack_check(hack_ctx* ctx);
+
+/* How a bf16 context forms the importance of hack_score / hack_step.
+ *   HACK_SCORE_FUSED     one launch that reads K once; the work-groups of a unit
+ *                        exchange their row sums inside the launch, which needs
+ *                        the whole launch resident on the device at once (the
+ *                        library sizes launches for an otherwise idle device).
+ *                        Default.
+ *   HACK_SCORE_TWO_PASS  two launches (row sums, then importance) that read K
+ *                        twice and never wait inside a kernel: safe when other
+ *                        streams or processes share the device.  Same results
+ *                        bit for bit.
+ * Switching drains the device (it re-arms the exchange workspace); do it
+ * outside stream captures.  fp32 contexts always score in two passes. */
+enum { HACK_SCORE_FUSED = 0, HACK_SCORE_TWO_PASS = 1 };
+hack_status hack_set_score_mode(hack_ctx* ctx, int32_t mode);
+int32_t hack_get_score_mode(const hack_ctx* ctx);
 
 /* ---- a1: importance estimation by subset attention --------------------
  * Sec. 4.4, "Importance Estimation via Efficient Subset Attention":

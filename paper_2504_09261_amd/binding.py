@@ -23,6 +23,7 @@ EXPORTS = [
     "hack_score", "hack_select", "hack_compact", "hack_attn", "hack_attn_variant",
     "hack_kvcache_rows_required", "hack_kvcache_create", "hack_kvcache_destroy",
     "hack_kvcache_reset", "hack_kvcache_view", "hack_step", "hack_head_variance",
+    "hack_set_score_mode", "hack_get_score_mode",
 ]
 
 
@@ -69,6 +70,9 @@ def load_library() -> C.CDLL:
     lib.hack_last_error.argtypes = [vp]
     lib.hack_last_error.restype = C.c_char_p
     lib.hack_check.argtypes = [vp]
+    lib.hack_set_score_mode.argtypes = [vp, i32]
+    lib.hack_get_score_mode.argtypes = [vp]
+    lib.hack_get_score_mode.restype = i32
     lib.hack_score.argtypes = [vp, i32, i32, vp, pi32, i32, f32, pcache, vp, pu8, vp, i64, vp]
     lib.hack_select.argtypes = [vp, i32, vp, i64, pi32, pu8, pi32, i32, i32, vp, i64, pi32, vp]
     lib.hack_compact.argtypes = [vp, i32, i32, pcache, vp, vp, i32, vp, i64, pcache, vp]
@@ -215,6 +219,13 @@ class Hack:
     def check(self):
         """Raise if a kernel of an earlier call reported a problem (synchronise first)."""
         self._check(self.lib.hack_check(self.ctx))
+
+    def set_score_mode(self, mode: int):
+        """0: fused single launch (default); 1: two launches without in-kernel waits."""
+        self._check(self.lib.hack_set_score_mode(self.ctx, mode))
+
+    def score_mode(self) -> int:
+        return int(self.lib.hack_get_score_mode(self.ctx))
 
     # ---- a1 ----
     def score(self, q, cache: Cache, scale: float, importance, k_new=None, q_idx=None, n_obs: Optional[int] = None,

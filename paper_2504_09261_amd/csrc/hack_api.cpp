@@ -4,6 +4,7 @@
 // and the kernel launches.  No device memory is ever read from the host.
 #include <algorithm>
 #include <cmath>
+#include <climits>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -15,6 +16,7 @@
 
 #include "../../include/hack.h"
 #include "hack_internal.h"
+#include "table_cache.h"
 
 using namespace hack;
 
@@ -23,15 +25,34 @@ using namespace hack;
 // ---------------------------------------------------------------------------
 namespace {
 
-constexpr size_t kArenaBytes = 32u << 20;  // launch tables (device + pinned mirror)
-constexpr size_t kAlign = 256;
+constexpr size_t kTableChunkBytes = 32u << 20;   // launch tables: one chunk (device memory + pinned mirror)
+constexpr size_t kTableLimitBytes = 1u << 30;    // ... and all chunks of a context together
 // Polls (each an atomic round trip plus a short sleep, ~1 us) a score wave spends waiting for the
 // other items of its unit before it gives up; real waits last a few microseconds.
 constexpr int kScoreSpinLimit = 1 << 18;
 
-struct TableEntry {
-  size_t offset;  // into both arenas
-  size_t bytes;
+// Launch-table storage in device memory with a pinned host mirror.
+struct HipTableBackend {
+  bool alloc(size_t bytes, uint8_t** dev, uint8_t** host) {
+    if (hipMalloc((void**)dev, bytes) != hipSuccess) return false;
+    if (hipHostMalloc((void**)host, bytes, hipHostMallocDefault) != hipSuccess) {
+      (void)hipFree(*dev);
+      return false;
+    }
+    return true;
+  }
+  void release(uint8_t* dev, uint8_t* host) {
+    (void)hipFree(dev);
+    (void)hipHostFree(host);
+  }
+  bool upload(uint8_t* dev, const uint8_t* host, size_t bytes, void* stream) {
+    return hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, static_cast<hipStream_t>(stream)) == hipSuccess;
+  }
+  bool may_alloc(void* stream) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    (void)hipStreamIsCapturing(static_cast<hipStream_t>(stream), &cs);
+    return cs == hipStreamCaptureStatusNone;
+  }
 };
 
 }  // namespace
@@ -46,6 +67,10 @@ struct hack_ctx {
   unsigned long long* rowstat = nullptr;  // bf16 path: [max_units, score_groups, 32] row-sum exchange slots, all-ones between launches
   int score_groups = 0;          // work-groups a unit of max_cache_len keys is scored by
   int spin_limit = 0;            // polls after which a score work-group gives up its wait for the unit's other work-groups
+  unsigned* abort_flag = nullptr; // bf16 path: device word behind the counters; set by a fused score launch that gave up
+  size_t n_slots = 0;            // 64-bit words in rowstat
+  int score_mode = HACK_SCORE_FUSED;   // hack_score_mode: fused single launch / two launches without in-kernel waits
+  int skip_publish = -1;         // test hook: work-group of a fused score launch that withholds its sums
   unsigned* counters = nullptr;  // bf16 path: [max_units, 2] reader counters, zero between launches
   float* hv_stats = nullptr;     // head variance: [max_units, max_queries, 2] softmax statistics of every query
   int* fault = nullptr;          // pinned, device-visible int[2]: [0] a score wave's bounded wait gave up (fatal),
@@ -55,11 +80,8 @@ struct hack_ctx {
   int split_max_items = 0;       // launches with at most this many 32-query attention items use the key-split kernel
   int64_t ws_stride = 0;
   int max_chunks = 0;
-  // launch-table cache
-  uint8_t* arena_dev = nullptr;
-  uint8_t* arena_host = nullptr;  // pinned
-  size_t arena_used = 0;
-  std::unordered_multimap<uint64_t, TableEntry> tables;
+  // launch-table cache: tables keep their device address for the life of the context
+  TableCache<HipTableBackend>* tables = nullptr;
   std::string err;
 };
 
@@ -102,15 +124,6 @@ hack_status fail(hack_ctx* ctx, hack_status s, const char* fmt, ...) {
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-uint64_t fnv1a(const uint8_t* p, size_t n) {
-  uint64_t h = 1469598103934665603ull;
-  for (size_t i = 0; i < n; ++i) {
-    h ^= p[i];
-    h *= 1099511628211ull;
-  }
-  return h;
-}
-
 // A launch table under construction: sections are appended 64-byte aligned.
 struct Table {
   std::vector<uint8_t> bytes;
@@ -124,37 +137,23 @@ struct Table {
 };
 
 // Returns the device address of a table with these contents, uploading it on
-// the given stream the first time it is seen.  Entries are immutable; both
-// copies live until the context is destroyed (or the arena is recycled).
+// the given stream the first time it is seen.  Tables are immutable and keep
+// their address until the context is destroyed, so queued kernels and captured
+// graphs may go on using them.
 hack_status table_device(hack_ctx* ctx, const Table& t, hipStream_t stream, const uint8_t** dev) {
-  const size_t n = t.bytes.size();
-  const uint64_t h = fnv1a(t.bytes.data(), n);
-  auto range = ctx->tables.equal_range(h);
-  for (auto it = range.first; it != range.second; ++it) {
-    if (it->second.bytes == n && memcmp(ctx->arena_host + it->second.offset, t.bytes.data(), n) == 0) {
-      *dev = ctx->arena_dev + it->second.offset;
-      return HACK_OK;
-    }
+  switch (ctx->tables->get(t.bytes.data(), t.bytes.size(), stream, dev)) {
+    case TableStatus::kOk: return HACK_OK;
+    case TableStatus::kTooLarge:
+      return fail(ctx, HACK_ECAPACITY, "launch table of %zu bytes exceeds the %zu-byte table chunk", t.bytes.size(), kTableChunkBytes);
+    case TableStatus::kFullDuringCapture:
+      return fail(ctx, HACK_ECAPACITY, "launch-table storage is full and cannot grow while the stream is being captured: "
+                                       "run the schedule once outside the capture first");
+    case TableStatus::kLimit:
+      return fail(ctx, HACK_ECAPACITY, "launch tables of this context exceed %zu bytes", kTableLimitBytes);
+    case TableStatus::kAllocFailed: return fail(ctx, HACK_EHIP, "allocating launch-table storage failed");
+    case TableStatus::kUploadFailed: return fail(ctx, HACK_EHIP, "uploading a launch table failed");
   }
-  const size_t need = (size_t)round_up((int64_t)n, kAlign);
-  if (need > kArenaBytes) return fail(ctx, HACK_ECAPACITY, "launch table of %zu bytes exceeds the arena", n);
-  if (ctx->arena_used + need > kArenaBytes) {
-    // Recycle: every table may still be referenced by queued work, so drain first.
-    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
-    (void)hipStreamIsCapturing(stream, &cs);
-    if (cs != hipStreamCaptureStatusNone)
-      return fail(ctx, HACK_ECAPACITY, "launch-table arena full during stream capture");
-    HIP_TRY(ctx, hipDeviceSynchronize());
-    ctx->tables.clear();
-    ctx->arena_used = 0;
-  }
-  const size_t off = ctx->arena_used;
-  memcpy(ctx->arena_host + off, t.bytes.data(), n);
-  HIP_TRY(ctx, hipMemcpyAsync(ctx->arena_dev + off, ctx->arena_host + off, n, hipMemcpyHostToDevice, stream));
-  ctx->arena_used += need;
-  ctx->tables.emplace(h, TableEntry{off, n});
-  *dev = ctx->arena_dev + off;
-  return HACK_OK;
+  return HACK_EHIP;
 }
 
 // Sec. 4.4 policies as index ranges (see hack_select in hack.h).
@@ -178,12 +177,33 @@ void plan_select(int type, int T, int b, int n_init, int n_recent, UnitDesc* d) 
   }
 }
 
+// Brings the exchange workspace of the fused score kernel back to its idle state
+// (every slot empty, counters and abort word zero).  Synchronises the device.
+hipError_t rearm_score_workspace(hack_ctx* ctx) {
+  hipError_t e = hipDeviceSynchronize();
+  if (e == hipSuccess && ctx->rowstat) e = hipMemset(ctx->rowstat, 0xFF, ctx->n_slots * sizeof(unsigned long long));
+  if (e == hipSuccess && ctx->counters) e = hipMemset(ctx->counters, 0, ((size_t)ctx->cfg.max_units * 2 + 64) * sizeof(unsigned));
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  return e;
+}
+
 // Conditions that kernels of earlier calls found on the device.
 hack_status device_report(hack_ctx* ctx) {
   volatile int* f = ctx->fault;
-  if (f && f[0])
-    return fail(ctx, HACK_EHIP, "an earlier score launch gave up waiting for a unit's work items; its importance "
-                                "output is incomplete and this context is no longer usable");
+  if (f && f[0]) {
+    // A fused score launch gave up its wait (the device did not keep the launch resident as a
+    // whole, e.g. because other work held compute units).  Later fused launches have refused to
+    // run since.  Recover: drain, re-arm the workspace, and from now on score in two launches
+    // that do not wait for each other inside a kernel.
+    if (rearm_score_workspace(ctx) != hipSuccess)
+      return fail(ctx, HACK_EHIP, "a score launch gave up its wait and the workspace could not be re-armed");
+    f[0] = 0;
+    ctx->score_mode = HACK_SCORE_TWO_PASS;
+    return fail(ctx, HACK_EHIP, "a score launch gave up waiting for a unit's other work-groups: importance (and whatever "
+                                "was derived from it) of the calls since the last successful check is incomplete and those "
+                                "calls must be issued again; the context has been re-armed and now scores in two passes "
+                                "without in-kernel waits");
+  }
   if (f && f[1]) {
     f[1] = 0;
     return fail(ctx, HACK_EUNSUPPORTED, "an earlier bf16 score launch met a logit beyond +-354 (scale * q.k); such logits "
@@ -289,6 +309,10 @@ void build_score_items(const std::vector<UnitDesc>& descs, const std::vector<int
 int plan_score_items(const hack_ctx* ctx, const std::vector<UnitDesc>& descs, const std::vector<int32_t>& list,
                      std::vector<ScoreItem>* items, std::vector<int>* group_begin) {
   const int small = score_item_keys(HACK_BF16), large = score_item_keys_large();
+  if (ctx->score_mode == HACK_SCORE_TWO_PASS) {   // no in-kernel wait: one launch pair holds any number of items
+    build_score_items(descs, list, small, INT32_MAX, items, group_begin);
+    return small;
+  }
   build_score_items(descs, list, small, ctx->score_capacity, items, group_begin);
   if (group_begin->size() <= 2 || ctx->score_capacity_large <= 0) return small;
   std::vector<ScoreItem> items_l;
@@ -313,9 +337,10 @@ void run_score(hack_ctx* ctx, hipStream_t s, const UnitDesc* ddev, const int32_t
     return;
   }
   for (size_t g = 0; g + 1 < group_begin.size(); ++g)
-    launch_score_fused(s, ctx->cfg.head_dim, item_keys, items_dev + group_begin[g], group_begin[g + 1] - group_begin[g], q,
-                       rows_dev, n_obs, N_k, scale, k_cache, k_new, ctx->rowstat, ctx->score_groups, ctx->counters, importance,
-                       imp_stride, ctx->fault, ctx->spin_limit);
+    launch_score_fused(s, ctx->cfg.head_dim, item_keys, ctx->score_mode == HACK_SCORE_TWO_PASS, items_dev + group_begin[g],
+                       group_begin[g + 1] - group_begin[g], q, rows_dev, n_obs, N_k, scale, k_cache, k_new, ctx->rowstat,
+                       ctx->score_groups, ctx->counters, importance, imp_stride, ctx->fault, ctx->spin_limit, ctx->abort_flag,
+                       ctx->skip_publish);
 }
 
 void fill_q_rows(const int32_t* q_idx, int n_obs, int N_k, int32_t* rows) {
@@ -346,6 +371,18 @@ extern "C" hack_status hack_check(hack_ctx* ctx) {
   return device_report(ctx);
 }
 
+extern "C" hack_status hack_set_score_mode(hack_ctx* ctx, int32_t mode) {
+  if (!ctx) return HACK_EINVAL;
+  if (mode != HACK_SCORE_FUSED && mode != HACK_SCORE_TWO_PASS) return fail(ctx, HACK_EINVAL, "unknown score mode %d", mode);
+  if (mode == ctx->score_mode) return HACK_OK;
+  // the two forms leave the exchange slots in different states: start the other one from a clean workspace
+  if (rearm_score_workspace(ctx) != hipSuccess) return fail(ctx, HACK_EHIP, "re-arming the score workspace failed");
+  ctx->score_mode = mode;
+  return HACK_OK;
+}
+
+extern "C" int32_t hack_get_score_mode(const hack_ctx* ctx) { return ctx ? ctx->score_mode : (int32_t)HACK_EINVAL; }
+
 extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (!out || !cfg) return HACK_EINVAL;
   *out = nullptr;
@@ -364,6 +401,10 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   ctx->spin_limit = kScoreSpinLimit;
   // test hook: a tiny limit makes the score kernel's bounded wait give up (every work-group still exits normally)
   if (const char* v = std::getenv("HACK_SCORE_SPIN_LIMIT")) ctx->spin_limit = std::max(0, std::atoi(v));
+  // test hook: this work-group of every fused score launch does not publish its row sums, so the work-groups of its
+  // unit run into the (tiny) spin limit deterministically
+  if (const char* v = std::getenv("HACK_SCORE_TEST_SKIP_PUBLISH")) ctx->skip_publish = std::atoi(v);
+  if (const char* v = std::getenv("HACK_SCORE_MODE")) ctx->score_mode = std::atoi(v) == 1 ? HACK_SCORE_TWO_PASS : HACK_SCORE_FUSED;
   if (const char* v = std::getenv("HACK_ATTN_SPLIT_ITEMS")) ctx->split_max_items = std::atoi(v);   // tuning / test override
   hipError_t e = hipSetDevice(cfg->device);
   const size_t n_ws = (size_t)cfg->max_units * ctx->ws_stride;
@@ -372,17 +413,22 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->stats, (size_t)cfg->max_units * ctx->max_chunks * kMaxObs * 2 * sizeof(double));
   ctx->score_groups = ((cfg->max_cache_len + score_item_keys(HACK_BF16) - 1) / score_item_keys(HACK_BF16) + 3) / 4;
   const size_t n_slots = (size_t)cfg->max_units * ctx->score_groups * kMaxObs;
+  ctx->n_slots = n_slots;
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->rowstat, n_slots * sizeof(unsigned long long));
-  if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, (size_t)cfg->max_units * 2 * sizeof(unsigned));
-  if (e == hipSuccess) e = hipMemset(ctx->counters, 0, (size_t)cfg->max_units * 2 * sizeof(unsigned));
+  const size_t n_counters = (size_t)cfg->max_units * 2 + 64;   // per-unit reader counters, then the abort word
+  if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, n_counters * sizeof(unsigned));
+  if (e == hipSuccess) e = hipMemset(ctx->counters, 0, n_counters * sizeof(unsigned));
+  if (e == hipSuccess) ctx->abort_flag = ctx->counters + (size_t)cfg->max_units * 2;
   if (e == hipSuccess && cfg->dtype == HACK_BF16)
     e = hipMalloc((void**)&ctx->hv_stats, (size_t)cfg->max_units * cfg->max_queries * 2 * sizeof(float));
   if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->fault, 2 * sizeof(int), hipHostMallocDefault);
   if (e == hipSuccess) ctx->fault[0] = ctx->fault[1] = 0;
   if (e == hipSuccess) e = hipMemset(ctx->rowstat, 0xFF, n_slots * sizeof(unsigned long long));   // every slot empty
   if (e == hipSuccess) e = hipDeviceSynchronize();
-  if (e == hipSuccess) e = hipMalloc((void**)&ctx->arena_dev, kArenaBytes);
-  if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->arena_host, kArenaBytes, hipHostMallocDefault);
+  if (e == hipSuccess) {
+    ctx->tables = new (std::nothrow) TableCache<HipTableBackend>(HipTableBackend{}, kTableChunkBytes, kTableLimitBytes);
+    if (!ctx->tables || !ctx->tables->reserve_first_chunk()) e = hipErrorOutOfMemory;
+  }
   if (e == hipSuccess && cfg->dtype == HACK_BF16) {
     // a unit's score items wait for each other inside one launch, so a launch may
     // hold at most as many items as the device keeps resident at once
@@ -408,8 +454,7 @@ extern "C" void hack_destroy(hack_ctx* ctx) {
   if (ctx->counters) (void)hipFree(ctx->counters);
   if (ctx->fault) (void)hipHostFree(ctx->fault);
   if (ctx->hv_stats) (void)hipFree(ctx->hv_stats);
-  if (ctx->arena_dev) (void)hipFree(ctx->arena_dev);
-  if (ctx->arena_host) (void)hipHostFree(ctx->arena_host);
+  delete ctx->tables;
   delete ctx;
 }
 

@@ -79,10 +79,16 @@ int score_item_keys(int dtype);
 int score_max_groups();   // work-groups per unit the fused kernel's exchange supports
 int score_item_keys_large();   // bf16: the larger item size, used when the default would not fit one launch
 int score_fused_capacity(int head_dim, int item_keys);
-void launch_score_fused(hipStream_t s, int head_dim, int item_keys, const ScoreItem* items, int n_items, const void* q,
-                        const int32_t* q_rows, int n_obs, int N_k, float scale, const void* k_cache,
+// two_pass: two launches (row sums, then importance) that read K twice but never wait inside
+// a launch, so n_items may then exceed the resident capacity and other kernels may share the
+// device.  abort_flag: DEVICE word, zero in normal operation; a fused launch that gave up its
+// wait sets it and later fused launches return at once until the host clears it.
+// skip_publish: -1, or (test hook) the work-group of the launch that withholds its sums.
+void launch_score_fused(hipStream_t s, int head_dim, int item_keys, bool two_pass, const ScoreItem* items, int n_items,
+                        const void* q, const int32_t* q_rows, int n_obs, int N_k, float scale, const void* k_cache,
                         const void* k_new, unsigned long long* slots, int slot_groups, unsigned* counters,
-                        float* importance, int64_t imp_stride, int* fault, int spin_limit);
+                        float* importance, int64_t imp_stride, int* fault, int spin_limit, const unsigned* abort_flag,
+                        int skip_publish);
 // fp32: two passes over (chunk of 256 keys, listed unit); list[n_list] indexes
 // descs; stats is a workspace of n_list * ceil(max_t_in / 256) * 64 doubles.
 void launch_score_generic(hipStream_t s, int head_dim, const UnitDesc* descs, const int32_t* list, int n_list,

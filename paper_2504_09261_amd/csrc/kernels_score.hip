@@ -262,13 +262,33 @@ __device__ __forceinline__ double half_sum_f64(double v) {
 // writing, and the host refuses further work on the context.  fault[1] reports
 // clamped logits.  Each work-group draws a ticket after it has read; the one that
 // draws the unit's last ticket marks the unit's slots empty again for the next launch.
-template <int D, int TILES>
+// A work-group that gives up also raises *abort_flag in device memory; every later
+// launch that finds it set leaves at once, before it reads any slot, so the sums a
+// failed launch left behind are never taken for valid ones.  The host clears the
+// flag when it re-arms the workspace.
+//
+// MODE selects what a launch does:
+//   kScoreFused   everything above, one launch;
+//   kScoreSums    A and B only: every work-group stores its row sums (pass 1 of 2);
+//   kScoreWrite   A again, then C with the sums pass 1 left (no waiting: pass 1 has
+//                 completed), pass 2 of 2.  The two-pass form reads K twice but does
+//                 not depend on the launch being resident as a whole.
+// skip_publish: test hook, index of a work-group of the launch that does not publish its
+// sums (-1: none); with a small spin_limit this makes the give-up path run
+// deterministically while every work-group still exits normally.
+enum : int { kScoreFused = 0, kScoreSums = 1, kScoreWrite = 2 };
+
+template <int D, int TILES, int MODE>
 __global__ __launch_bounds__(kThreads, 2) void score_fused(
     const ScoreItem* __restrict__ items, int n_items, const __bf16* __restrict__ q,
     const int32_t* __restrict__ q_rows, int n_obs, int N_k, float scale,
     const __bf16* __restrict__ k_cache, const __bf16* __restrict__ k_new,
     unsigned long long* __restrict__ slots, int slot_groups, unsigned* __restrict__ counters,
-    float* __restrict__ importance, int64_t imp_stride, int* __restrict__ fault, int spin_limit) {
+    float* __restrict__ importance, int64_t imp_stride, int* __restrict__ fault, int spin_limit,
+    const unsigned* __restrict__ abort_flag_in, int skip_publish) {
+  unsigned* abort_flag = const_cast<unsigned*>(abort_flag_in);
+  // read now, acted upon once the loads of the Q~ fragments have been waited for anyway
+  const unsigned aborted = (MODE == kScoreFused) ? __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0u;
   constexpr int KK = D / 16;            // MFMA steps over the head dimension
   constexpr int CPR = D / 8;            // 16-byte chunks per row
   constexpr int RPI = 64 / CPR;         // rows per wave-wide copy instruction
@@ -342,6 +362,11 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
   // consumed, so that no compiler-placed vmcnt wait also drains the tile copies
 #pragma unroll
   for (int kk = 0; kk < KK; ++kk) asm volatile("" ::"v"(qf[kk]));
+  if (MODE == kScoreFused && __builtin_amdgcn_readfirstlane(aborted) != 0) {
+    // an earlier launch gave up: its sums may still sit in the slots, so nothing here may be trusted
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the first tile's copy must not outlive the wave
+    return;
+  }
 
   int k_off[KK];
 #pragma unroll
@@ -402,6 +427,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
   // the work-group: every wave leaves its 32 row sums there, wave 0 adds the four
   // and publishes one value per row.
   double* red = reinterpret_cast<double*>(&tiles[w][0][0]);
+  if (MODE != kScoreWrite)
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     double lsum = 0.0;
@@ -412,13 +438,14 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
     if (col == 0) red[c_row(r, half)] = l;
   }
   __syncthreads();
-  if (w == 0 && lane < kMaxObs) {
+  if (MODE != kScoreWrite && w == 0 && lane < kMaxObs && (int)blockIdx.x != skip_publish) {
     double tot = 0.0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) tot += reinterpret_cast<const double*>(&tiles[k][0][0])[lane];
     __hip_atomic_store(&unit_slots[group * kMaxObs + lane], (unsigned long long)__double_as_longlong(tot),
                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  if (MODE == kScoreSums) return;
   // ---- C: collect the unit's slots ---------------------------------------------
   // thread (sub, row) = (tid / 32, tid % 32) takes work-groups sub, sub + 8, ... of row `row`
   double* part8 = reinterpret_cast<double*>(&tiles[1][0][0]) + 64;   // [8][32] partial sums, behind wave 1's row sums
@@ -442,7 +469,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
 #pragma unroll
     for (int k = 0; k < kMaxGroups / 8; ++k) {
       int polls = 0;
-      while (bits[k] == kEmpty) {
+      while (MODE == kScoreFused && bits[k] == kEmpty) {
         if (++polls > spin_limit) { ok = false; break; }
         __builtin_amdgcn_s_sleep(8);
         bits[k] = __hip_atomic_load(&unit_slots[(sub + 8 * k) * kMaxObs + row], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -454,11 +481,14 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
   }
   __syncthreads();
   if (*ok_s == 0) {
-    if (tid == 0) __hip_atomic_store(fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (tid == 0) {
+      __hip_atomic_store(abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
     return;
   }
   unsigned ticket = 0;
-  if (w == 0) {
+  if (MODE == kScoreFused && w == 0) {
     if (lane < kMaxObs) {
       double l = 0.0;
 #pragma unroll
@@ -468,6 +498,12 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
     // every slot this work-group needed has been read (the values were used above):
     // whoever draws the last ticket may mark the slots empty without racing a reader
     if (lane == 0) ticket = atomicAdd(&cnt[1], 1u);
+  }
+  if (MODE == kScoreWrite && w == 0 && lane < kMaxObs) {
+    double l = 0.0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) l += part8[k * kMaxObs + lane];
+    inv_s[lane] = (lane < n_obs) ? 1.0 / l : 0.0;
   }
   __syncthreads();
   double inv_r[16];
@@ -485,7 +521,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
       if (j < T_in && half == 0) importance[(int64_t)it.unit * imp_stride + j] = (float)imp;
     }
   }
-  if (w == 0) {
+  if (MODE == kScoreFused && w == 0) {
     // the work-group that drew a unit's last ticket leaves slots and counter as the next launch expects them
     ticket = __builtin_amdgcn_readfirstlane(ticket);
     if ((int)ticket == it.n_groups - 1) {
@@ -521,33 +557,53 @@ int score_fused_capacity(int head_dim, int item_keys) {
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
   hipError_t e;
   if (item_keys == kItemKeysLarge)
-    e = head_dim == 64 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<64, 8>, kThreads, 0)
-                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<128, 8>, kThreads, 0);
+    e = head_dim == 64 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<64, 8, kScoreFused>, kThreads, 0)
+                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<128, 8, kScoreFused>, kThreads, 0);
   else
-    e = head_dim == 64 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<64, 4>, kThreads, 0)
-                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<128, 4>, kThreads, 0);
+    e = head_dim == 64 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<64, 4, kScoreFused>, kThreads, 0)
+                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<128, 4, kScoreFused>, kThreads, 0);
   if (e != hipSuccess) return 0;
   return blocks * cus * (kThreads / 64);
 }
 
-void launch_score_fused(hipStream_t s, int head_dim, int item_keys, const ScoreItem* items, int n_items, const void* q,
-                        const int32_t* q_rows, int n_obs, int N_k, float scale, const void* k_cache,
+template <int D, int TILES>
+static void launch_score_t(hipStream_t s, dim3 grid, bool two_pass, const ScoreItem* items, int n_items, const __bf16* q,
+                           const int32_t* q_rows, int n_obs, int N_k, float scale, const __bf16* k_cache,
+                           const __bf16* k_new, unsigned long long* slots, int slot_groups, unsigned* counters,
+                           float* importance, int64_t imp_stride, int* fault, int spin_limit,
+                           const unsigned* abort_flag, int skip_publish) {
+#define HACK_SCORE_ARGS grid, dim3(kThreads), 0, s, items, n_items, q, q_rows, n_obs, N_k, scale, k_cache, k_new, slots, \
+                        slot_groups, counters, importance, imp_stride, fault, spin_limit, abort_flag, skip_publish
+  if (two_pass) {
+    hipLaunchKernelGGL((score_fused<D, TILES, kScoreSums>), HACK_SCORE_ARGS);
+    hipLaunchKernelGGL((score_fused<D, TILES, kScoreWrite>), HACK_SCORE_ARGS);
+  } else {
+    hipLaunchKernelGGL((score_fused<D, TILES, kScoreFused>), HACK_SCORE_ARGS);
+  }
+#undef HACK_SCORE_ARGS
+}
+
+void launch_score_fused(hipStream_t s, int head_dim, int item_keys, bool two_pass, const ScoreItem* items, int n_items,
+                        const void* q, const int32_t* q_rows, int n_obs, int N_k, float scale, const void* k_cache,
                         const void* k_new, unsigned long long* slots, int slot_groups, unsigned* counters,
-                        float* importance, int64_t imp_stride, int* fault, int spin_limit) {
+                        float* importance, int64_t imp_stride, int* fault, int spin_limit, const unsigned* abort_flag,
+                        int skip_publish) {
   if (n_items <= 0) return;
   typedef __bf16 T;
   dim3 grid((n_items + 3) / 4);
-#define HACK_SCORE_ARGS grid, dim3(kThreads), 0, s, items, n_items, (const T*)q, q_rows, n_obs, N_k, scale, (const T*)k_cache, \
-                        (const T*)k_new, slots, slot_groups, counters, importance, imp_stride, fault, spin_limit
+#define HACK_SCORE_CALL(D_, TILES_)                                                                                   \
+  launch_score_t<D_, TILES_>(s, grid, two_pass, items, n_items, (const T*)q, q_rows, n_obs, N_k, scale, (const T*)k_cache, \
+                             (const T*)k_new, slots, slot_groups, counters, importance, imp_stride, fault, spin_limit,  \
+                             abort_flag, skip_publish)
   const bool large = item_keys == kItemKeysLarge;
   if (head_dim == 64) {
-    if (large) hipLaunchKernelGGL((score_fused<64, 8>), HACK_SCORE_ARGS);
-    else hipLaunchKernelGGL((score_fused<64, 4>), HACK_SCORE_ARGS);
+    if (large) HACK_SCORE_CALL(64, 8);
+    else HACK_SCORE_CALL(64, 4);
   } else {
-    if (large) hipLaunchKernelGGL((score_fused<128, 8>), HACK_SCORE_ARGS);
-    else hipLaunchKernelGGL((score_fused<128, 4>), HACK_SCORE_ARGS);
+    if (large) HACK_SCORE_CALL(128, 8);
+    else HACK_SCORE_CALL(128, 4);
   }
-#undef HACK_SCORE_ARGS
+#undef HACK_SCORE_CALL
 }
 
 void launch_score_generic(hipStream_t s, int head_dim, const UnitDesc* descs, const int32_t* list, int n_list,

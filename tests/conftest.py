@@ -26,3 +26,15 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_terminal_summary(terminalreporter):
+    # whole-schedule parity statistics (exact / excused / mismatch kept sets, max |dO|) of the GPU runs
+    try:
+        from tests import test_gpu_schedule as t
+    except Exception:  # pragma: no cover
+        return
+    if t.PARITY_LOG:
+        terminalreporter.write_sep("-", "device-vs-oracle parity statistics")
+        for line in t.PARITY_LOG:
+            terminalreporter.write_line(line)

@@ -22,6 +22,8 @@ def to_dev(x_f32: np.ndarray, dtype: str) -> torch.Tensor:
 
 
 def from_dev(t: torch.Tensor) -> np.ndarray:
+    """Device tensor -> float64 host array.  Call it on the rows a unit owns (slices of a slab
+    that was allocated uninitialised hold arbitrary bit patterns outside those rows)."""
     return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
 
 
@@ -75,28 +77,5 @@ def make_hack(cfg_or_none=None, *, heads=None, head_dim=None, dtype=None, max_un
                 os.environ["HACK_ATTN_SPLIT_ITEMS"] = saved
 
 
-def kept_set_verdict(I_gpu: np.ndarray, I_ref: np.ndarray, imp_ref: np.ndarray, sel_lo: int, sel_hi: int, m: int):
-    """'exact', 'excused' (every differing index is a near-tie: oracle importance
-    within 1e-6 relative of the oracle's m-th largest of the ranked segment) or 'mismatch'."""
-    if np.array_equal(I_gpu, I_ref):
-        return "exact"
-    if len(I_gpu) != len(I_ref) or np.any(np.diff(I_gpu) <= 0):
-        return "mismatch"
-    diff = np.setxor1d(I_gpu, I_ref)
-    if np.any(diff < sel_lo) or np.any(diff >= sel_hi) or m <= 0:
-        return "mismatch"
-    seg = np.sort(imp_ref[sel_lo:sel_hi])[::-1]
-    thr = seg[m - 1]
-    ok = np.all(np.abs(imp_ref[diff] - thr) <= 1e-6 * abs(thr))
-    return "excused" if ok else "mismatch"
-
-
-def ranked_segment(head_type: int, T: int, b: int, n_init: int, N_k: int):
-    """(sel_lo, sel_hi, m) of the ranked segment, restated from Sec. 4.4 for the verdict helper."""
-    if head_type == ho.CONTEXTUAL:
-        return 0, T, b
-    n0 = min(n_init, T - N_k)
-    M = b - n0 - N_k
-    if M >= 0:
-        return n0, T - N_k, M
-    return T - N_k, T, b - min(n0, b)
+# the verdict rules live with the oracle-side checker (pure numpy)
+from oracle.parity import kept_set_verdict, ranked_segment  # noqa: E402,F401

@@ -388,43 +388,93 @@ def test_attention_variant_query_matches_the_documented_rule():
     hk.close()
 
 
-def test_score_bounded_wait_gives_up_and_is_reported(monkeypatch):
-    """The in-kernel wait of the bf16 score kernel is bounded.  With the poll limit forced to zero
-    from the host, a work-group that finds another one's row sums not yet published gives up at
-    once: every work-group still exits normally, the condition is raised in the host-visible
-    flag, hack_check reports it and the context refuses further work."""
+def test_score_give_up_is_contained_reported_and_recovered(monkeypatch):
+    """The in-kernel wait of the fused bf16 score kernel is bounded.  A host-side test hook makes
+    one work-group of every fused launch withhold its row sums and sets a small poll limit, so the
+    work-groups of that unit give up deterministically while every kernel still exits normally.
+    Then: the condition is raised; a fused launch queued after the failing one does not consume
+    what it left in the exchange slots (it writes nothing); the call that reports the failure
+    re-arms the workspace and switches the context to the two-pass form; the same context then
+    gives the right importance again."""
     u = _u()
-    monkeypatch.setenv("HACK_SCORE_SPIN_LIMIT", "0")
+    monkeypatch.setenv("HACK_SCORE_SPIN_LIMIT", "8")
+    monkeypatch.setenv("HACK_SCORE_TEST_SKIP_PUBLISH", "3")
     rng = np.random.default_rng(9)
-    H, d, dtype, Nk = 4, 128, "bf16", 64
+    H, d, dtype, Nk, L = 4, 128, "bf16", 64, 8000
     hk = u.make_hack(heads=H, head_dim=d, dtype=dtype, max_units=H, max_cache_len=8192, max_queries=Nk)
     monkeypatch.delenv("HACK_SCORE_SPIN_LIMIT")
-    rows = [(u.rand_values(rng, (8000, d), dtype), u.rand_values(rng, (8, d), dtype)[:0]) for _ in range(H)]
-    K = np.zeros((H * 8000, d), np.float32)
-    for i, (k, _) in enumerate(rows):
-        K[i * 8000:(i + 1) * 8000] = k
+    monkeypatch.delenv("HACK_SCORE_TEST_SKIP_PUBLISH")
+    assert hk.score_mode() == 0
+    K = u.rand_values(rng, (H * L, d), dtype)
     Kd = u.to_dev(K, dtype)
-    cin = Cache(Kd, Kd, np.arange(H, dtype=np.int64) * 8000, np.full(H, 8000, np.int32))
-    q = u.to_dev(u.rand_values(rng, (1, H, Nk, d), dtype), dtype)
-    imp = torch.zeros((H, 8192), device=u.DEV)
-    gave_up = False
-    for _ in range(5):                      # 16 work-groups per unit: the first to arrive practically always finds an empty slot
-        try:
-            hk.score(q, cin, 0.05, imp)
-            torch.cuda.synchronize()
-            hk.check()
-        except HackError as e:
-            assert e.status == -4
-            gave_up = True
-            break
-    assert gave_up
-    with pytest.raises(HackError):          # the context stays refused
-        hk.score(q, cin, 0.05, imp)
-    hk.close()
-    # a fresh context with the normal limit works on the same inputs
-    hk = u.make_hack(heads=H, head_dim=d, dtype=dtype, max_units=H, max_cache_len=8192, max_queries=Nk)
-    hk.score(q, cin, 0.05, imp)
+    cin = Cache(Kd, Kd, np.arange(H, dtype=np.int64) * L, np.full(H, L, np.int32))
+    q = u.rand_values(rng, (1, H, Nk, d), dtype)
+    qd = u.to_dev(q, dtype)
+    scale = 0.05
+    imp1 = torch.full((H, 8192), -1.0, device=u.DEV)
+    imp2 = torch.full((H, 8192), -1.0, device=u.DEV)
+    hk.score(qd, cin, scale, imp1)           # one unit of this launch never gets all its sums
+    hk.score(qd, cin, scale, imp2)           # queued behind it: must leave without reading the slots
+    torch.cuda.synchronize()
+    assert torch.all(imp2 == -1.0)           # nothing was formed from stale sums
+    with pytest.raises(HackError) as ei:
+        hk.check()
+    assert ei.value.status == -4
+    assert hk.score_mode() == 1              # recovered into the form without in-kernel waits
+    hk.check()                               # reported once
+    imp3 = torch.full((H, 8192), -1.0, device=u.DEV)
+    hk.score(qd, cin, scale, imp3)
     torch.cuda.synchronize()
     hk.check()
-    assert abs(float(imp[0].sum()) - 32.0) < 1e-3
+    got = imp3.cpu().numpy().astype(np.float64)
+    obs = ho.observation_rows(Nk, 32)
+    for uu in range(H):
+        want = ho.importance(q[0, uu][obs].astype(np.float64), K[uu * L:(uu + 1) * L].astype(np.float64), scale)
+        assert float(np.max(np.abs(got[uu, :L] - want) / want)) < 1e-6, uu
+        assert np.all(got[uu, L:] == -1.0)
+    hk.close()
+    # a fresh context without the hook works in the fused form on the same inputs, with the same bits
+    hk = u.make_hack(heads=H, head_dim=d, dtype=dtype, max_units=H, max_cache_len=8192, max_queries=Nk)
+    imp4 = torch.full((H, 8192), -1.0, device=u.DEV)
+    hk.score(qd, cin, scale, imp4)
+    torch.cuda.synchronize()
+    hk.check()
+    assert hk.score_mode() == 0 and torch.equal(imp3, imp4)
+    hk.close()
+
+
+def test_score_two_pass_form_matches_fused_bit_for_bit_and_holds_any_number_of_items():
+    """hack_set_score_mode: the two-pass form (no in-kernel waits) gives the same importance bit
+    for bit, also where the fused form has to cut the work into several launches, and switching
+    back and forth leaves the exchange workspace usable."""
+    u = _u()
+    rng = np.random.default_rng(15)
+    H, B, d, Nk, dtype = 16, 5, 128, 48, "bf16"
+    U = H * B
+    lens = [int(x) for x in rng.integers(3500, 4200, U)]
+    lens[3], lens[40] = 0, 77
+    hk = u.make_hack(heads=H, head_dim=d, dtype=dtype, max_units=U, max_cache_len=4352, max_queries=Nk)
+    rows = [(u.rand_values(rng, (n, d), dtype),) * 2 for n in lens]
+    cin, _ = u.build_cache(rows, d, dtype)
+    q, k_new = u.rand_values(rng, (B, H, Nk, d), dtype) * 1.5, u.rand_values(rng, (B, H, Nk, d), dtype)
+    qd, kd = u.to_dev(wl.bf16_to_f32(wl.bf16_round(q)), dtype), u.to_dev(k_new, dtype)
+    scale = float(np.float32(1.0 / np.sqrt(d)))
+    out = []
+    for mode in (0, 1, 0, 1):
+        hk.set_score_mode(mode)
+        imp = torch.full((U, 4352), -1.0, device=u.DEV)
+        hk.score(qd, cin, scale, imp, k_new=kd)
+        torch.cuda.synchronize()
+        hk.check()
+        out.append(imp)
+    for o in out[1:]:
+        assert torch.equal(out[0], o)
+    got = out[1].cpu().numpy().astype(np.float64)
+    obs = ho.observation_rows(Nk, 32)
+    qh = wl.bf16_to_f32(wl.bf16_round(q))
+    for uu in (0, 3, 40, U - 1):
+        b, h = divmod(uu, H)
+        K_in = np.concatenate([rows[uu][0], k_new[b, h]]).astype(np.float64)
+        want = ho.importance(qh[b, h][obs].astype(np.float64), K_in, scale)
+        assert float(np.max(np.abs(got[uu, :len(want)] - want) / want)) < 1e-6, uu
     hk.close()
