@@ -26,7 +26,15 @@ Readings taken where the paper is silent:
   * the ranking is decided on importance rounded to float32, the precision in
     which the device stores it, so that both sides decide on the same numbers;
   * the attention variance of the head classification is the population
-    variance; alpha * L * H is rounded to the nearest integer.
+    variance; alpha * L * H is rounded to the nearest integer;
+  * the final-step merge of contextual heads (the paper names the operation and
+    defers its definition to another work: parity unpinned against that work):
+    similarity = cosine similarity between key rows; an evicted row's nearest
+    retained counterpart = the kept row of highest similarity (ties to the lower
+    index, decided on similarities rounded to float32, the device's precision);
+    the kept row becomes the weighted average of itself (weight 1) and the rows
+    merged into it (weight = their similarity, negative ones count as 0), keys
+    and values with the same weights.
 
 Pinned by tests/test_oracle_pins.py (brute force in pure Python on tiny
 inputs, closed forms, invariants, the full-budget reduction to plain attention
@@ -167,14 +175,52 @@ def attention(Q: np.ndarray, K: np.ndarray, V: np.ndarray, scale: float) -> np.n
 
 
 # ---------------------------------------------------------------------------
+# Sec. 4.4, paragraph after the f_C equation: merge at the final generation step
+# ---------------------------------------------------------------------------
+def key_similarity(K_a: np.ndarray, K_b: np.ndarray) -> np.ndarray:
+    """Cosine similarity between every row of K_a and every row of K_b (a row of
+    zero norm is similar to nothing: 0)."""
+    na = np.sqrt((K_a * K_a).sum(axis=1))
+    nb = np.sqrt((K_b * K_b).sum(axis=1))
+    S = K_a @ K_b.T
+    den = na[:, None] * nb[None, :]
+    return np.divide(S, den, out=np.zeros_like(S), where=den > 0)
+
+
+def merge_final(K: np.ndarray, V: np.ndarray, I: np.ndarray):
+    """Discarded rows are folded into their nearest retained counterparts by
+    similarity-weighted averaging.  K, V [T, d]: the uncompressed cache of the step;
+    I: ascending kept indices.  Returns (K^, V^, nearest, weight): the merged kept
+    rows, and for every evicted row (ascending) the position in I of the row it
+    was merged into and the weight it entered with."""
+    T = K.shape[0]
+    I = np.asarray(I, dtype=np.int64)
+    evicted = np.setdiff1d(np.arange(T, dtype=np.int64), I)
+    K_hat, V_hat = K[I].copy(), V[I].copy()
+    if evicted.size == 0:
+        return K_hat, V_hat, np.zeros(0, np.int64), np.zeros(0)
+    S = key_similarity(K[evicted], K[I])
+    nearest = np.argmax(S.astype(np.float32), axis=1)           # first maximum = lowest kept index
+    weight = np.maximum(S[np.arange(evicted.size), nearest], 0.0)
+    total = np.ones(I.size)                                      # the kept row itself enters with weight 1
+    np.add.at(K_hat, nearest, weight[:, None] * K[evicted])
+    np.add.at(V_hat, nearest, weight[:, None] * V[evicted])
+    np.add.at(total, nearest, weight)
+    return K_hat / total[:, None], V_hat / total[:, None], nearest.astype(np.int64), weight
+
+
+# ---------------------------------------------------------------------------
 # one unit = one (batch, head) pair
 # ---------------------------------------------------------------------------
 def unit_step(Kc, Vc, Pc, Qk, Kk, Vk, pos0, head_type, budget, N_init, scale,
-              N_obs=32, q_rows=None):
+              N_obs=32, q_rows=None, final_merge=False):
     """One scale step of one unit.
 
     Kc, Vc [L, d]: cache before the step;  Pc [L]: global token ids of its rows
     Qk, Kk, Vk [N_k, d]: this scale;       pos0: global id of this scale's first token
+    final_merge: this is the last generation step; a contextual head that compresses
+    merges what it discards into what it keeps (supplementary, Compression Setting:
+    only f_C, only the final step).
     Returns dict(K, V, pos, O, imp, I, compressed).
     """
     N_k = Qk.shape[0]
@@ -189,18 +235,22 @@ def unit_step(Kc, Vc, Pc, Qk, Kk, Vk, pos0, head_type, budget, N_init, scale,
         rows = observation_rows(N_k, N_obs) if q_rows is None else np.asarray(q_rows)
         imp = importance(Qk[rows], K_in, scale)
         I = select(imp, head_type, budget, N_init, N_k)
-        K_in, V_in = compact(K_in, V_in, I)
+        if final_merge and head_type == CONTEXTUAL:
+            K_in, V_in, _, _ = merge_final(K_in, V_in, I)
+        else:
+            K_in, V_in = compact(K_in, V_in, I)
         P_in = P_in[I]
     O = attention(Qk, K_in, V_in, scale)
     return dict(K=K_in, V=V_in, pos=P_in, O=O, imp=imp, I=I, compressed=compressed)
 
 
 def run_schedule(steps, head_types, budgets_per_step, N_init, scale, N_obs=32,
-                 units=None, keep_outputs=True):
+                 units=None, keep_outputs=True, final_merge=False):
     """Whole scale schedule of one layer.
 
     steps: list of (Q, K, V) float arrays [B, H, N_k, d], one per scale
     head_types: [H]; budgets_per_step: list of int arrays [B*H]
+    final_merge: contextual heads merge at the last step of `steps` (see unit_step)
     Returns per step a list of per-unit dicts (see unit_step); evicted rows never
     come back (supplementary, Compression Setting).
     """
@@ -219,7 +269,8 @@ def run_schedule(steps, head_types, budgets_per_step, N_init, scale, N_obs=32,
             r = unit_step(Kc, Vc, Pc,
                           np.asarray(Q[b, h], np.float64), np.asarray(K[b, h], np.float64),
                           np.asarray(V[b, h], np.float64), pos0, int(head_types[h]),
-                          int(budgets_per_step[k][u]), N_init, scale, N_obs)
+                          int(budgets_per_step[k][u]), N_init, scale, N_obs,
+                          final_merge=final_merge and k == len(steps) - 1)
             state[u] = (r["K"], r["V"], r["pos"])
             if not keep_outputs:
                 r = dict(pos=r["pos"], I=r["I"], compressed=r["compressed"], len=r["K"].shape[0])

@@ -44,6 +44,11 @@ def _run_pins():
         call("head_variance_pure_python", pins.test_head_variance_matches_pure_python, *prm)
     call("head_variance_closed_forms", pins.test_head_variance_closed_forms_and_invariants)
     call("classify_heads", pins.test_classify_heads_hand_computed_and_planted_mask)
+    for prm in [(0, 9, 4, 5), (1, 14, 3, 8), (2, 6, 5, 3), (3, 12, 1, 4)]:
+        call("merge_pure_python", pins.test_merge_matches_pure_python, *prm)
+    call("merge_hand", pins.test_merge_hand_computed_four_keys)
+    call("merge_properties", pins.test_merge_properties)
+    call("merge_final_step_only", pins.test_merge_happens_only_for_contextual_heads_at_the_final_step)
     return failed
 
 
@@ -207,6 +212,63 @@ _orig_topk = ho.topk_indices
 _orig_classify = ho.classify_heads
 _orig_structural = ho.select_structural
 
+def _merge_with(sim=None, pick=np.argmax, clip=True, own_weight=1.0, v_uniform=False):
+    """merge_final rebuilt from its steps with one of them replaced."""
+    def merge(K, V, I):
+        T = K.shape[0]
+        I = np.asarray(I, dtype=np.int64)
+        ev = np.setdiff1d(np.arange(T, dtype=np.int64), I)
+        Kh, Vh = K[I].copy(), V[I].copy()
+        if ev.size == 0:
+            return Kh, Vh, np.zeros(0, np.int64), np.zeros(0)
+        S = (sim or ho.key_similarity)(K[ev], K[I])
+        nearest = pick(S, axis=1)
+        w = S[np.arange(ev.size), nearest]
+        if clip:
+            w = np.maximum(w, 0.0)
+        tot = np.full(I.size, own_weight)
+        Kh, Vh = Kh * own_weight, Vh * own_weight
+        np.add.at(Kh, nearest, w[:, None] * K[ev])
+        np.add.at(Vh, nearest, (np.ones_like(w) if v_uniform else w)[:, None] * V[ev])
+        np.add.at(tot, nearest, w)
+        return Kh / tot[:, None], Vh / tot[:, None], nearest.astype(np.int64), w
+    return merge
+
+
+def _merge_farthest(K, V, I):
+    return _merge_with(pick=np.argmin)(K, V, I)
+
+
+def _merge_plain_dot_similarity(K, V, I):
+    return _merge_with(sim=lambda A, B: A @ B.T)(K, V, I)
+
+
+def _merge_negative_weights_kept(K, V, I):
+    return _merge_with(clip=False)(K, V, I)
+
+
+def _merge_kept_row_without_own_weight(K, V, I):
+    return _merge_with(own_weight=1e-9)(K, V, I)
+
+
+def _merge_values_unweighted(K, V, I):
+    return _merge_with(v_uniform=True)(K, V, I)
+
+
+def _merge_is_a_plain_gather(K, V, I):            # the merge forgotten
+    I = np.asarray(I, dtype=np.int64)
+    return K[I], V[I], np.zeros(0, np.int64), np.zeros(0)
+
+
+def _merge_ties_to_higher_index(K, V, I):
+    return _merge_with(pick=lambda S, axis: S.shape[1] - 1 - np.argmax(S[:, ::-1], axis=axis))(K, V, I)
+
+
+def _similarity_unnormalised_by_one_side(K_a, K_b):
+    nb = np.sqrt((K_b * K_b).sum(axis=1))
+    return (K_a @ K_b.T) / nb[None, :]
+
+
 MUTANTS = [
     ("softmax_rows", _softmax_no_normaliser),
     ("softmax_rows", _softmax_over_queries),
@@ -237,6 +299,14 @@ MUTANTS = [
     ("head_variance", _variance_mean_over_columns),
     ("classify_heads", _classify_high_variance_is_contextual),
     ("classify_heads", _classify_per_layer_ranking),
+    ("merge_final", _merge_farthest),
+    ("merge_final", _merge_plain_dot_similarity),
+    ("merge_final", _merge_negative_weights_kept),
+    ("merge_final", _merge_kept_row_without_own_weight),
+    ("merge_final", _merge_values_unweighted),
+    ("merge_final", _merge_is_a_plain_gather),
+    ("merge_final", _merge_ties_to_higher_index),
+    ("key_similarity", _similarity_unnormalised_by_one_side),
 ]
 
 
@@ -245,6 +315,31 @@ def test_planted_mistake_is_caught(monkeypatch, target, mutant):
     monkeypatch.setattr(ho, target, mutant)
     failed = _run_pins()
     assert failed, f"no pin noticed {mutant.__name__} planted into oracle.{target}"
+
+
+def test_merge_at_the_wrong_place_is_caught(monkeypatch):
+    """A schedule that merges for structural heads too, or at every step."""
+    orig = ho.unit_step
+
+    def merge_everywhere(Kc, Vc, Pc, Qk, Kk, Vk, pos0, head_type, budget, N_init, scale, *a, **kw):
+        kw = dict(kw)
+        if "final_merge" in kw or len(a) >= 3:
+            kw["final_merge"] = True
+            a = a[:2]
+        return orig(Kc, Vc, Pc, Qk, Kk, Vk, pos0, head_type, budget, N_init, scale, *a, **kw)
+
+    def merge_structural(Kc, Vc, Pc, Qk, Kk, Vk, pos0, head_type, budget, N_init, scale, *a, **kw):
+        r = dict(orig(Kc, Vc, Pc, Qk, Kk, Vk, pos0, head_type, budget, N_init, scale, *a, **kw))
+        if kw.get("final_merge") and head_type == ho.STRUCTURAL and r["compressed"]:
+            K_in, V_in = np.concatenate([Kc, Kk]), np.concatenate([Vc, Vk])
+            r["K"], r["V"], _, _ = ho.merge_final(K_in, V_in, r["I"])
+            r["O"] = ho.attention(Qk, r["K"], r["V"], scale)
+        return r
+
+    for planted in (merge_everywhere, merge_structural):
+        monkeypatch.setattr(ho, "unit_step", planted)
+        failed = _run_pins()
+        assert "merge_final_step_only" in failed, (planted.__name__, failed)
 
 
 def test_compress_after_attention_is_caught(monkeypatch):

@@ -412,3 +412,130 @@ def test_classify_heads_hand_computed_and_planted_mask():
                     for h in range(cfg.heads)])
     assert np.array_equal(ho.classify_heads(sig, float((types == 0).mean())), types)
     assert sig[types == 0].max() * 20 < sig[types == 1].min()                 # a clear boundary, as the paper describes
+
+
+# ---------------------------------------------------------------------------
+# final-step merge of contextual heads (Sec. 4.4, paragraph after the f_C equation;
+# supplementary, Compression Setting).  The paper names the operation and defers its
+# definition to another work, so these pins fix OUR reading (cosine similarity of keys,
+# nearest kept row, weights = similarity clipped at 0, the kept row itself with weight 1)
+# and what any reading of "similarity-weighted averaging into the nearest retained
+# counterpart" must satisfy; parity with the cited work is unpinned.
+# ---------------------------------------------------------------------------
+def bf_merge(K, V, I):
+    """Pure-Python restatement: loops, math.sqrt / fsum only."""
+    T, kept = len(K), list(int(i) for i in I)
+    norm = [math.sqrt(bf_dot(k, k)) for k in K]
+    num_k = {r: [[float(x)] for x in K[r]] for r in kept}
+    num_v = {r: [[float(x)] for x in V[r]] for r in kept}
+    den = {r: [1.0] for r in kept}
+    for e in range(T):
+        if e in kept:
+            continue
+        best, best_s = None, None
+        for r in kept:
+            s = bf_dot(K[e], K[r]) / (norm[e] * norm[r]) if norm[e] * norm[r] > 0 else 0.0
+            if best is None or s > best_s:          # strict: the lower index keeps a tie
+                best, best_s = r, s
+        w = max(best_s, 0.0)
+        for c in range(len(K[0])):
+            num_k[best][c].append(w * float(K[e][c]))
+        for c in range(len(V[0])):
+            num_v[best][c].append(w * float(V[e][c]))
+        den[best].append(w)
+    Kh = [[math.fsum(col) / math.fsum(den[r]) for col in num_k[r]] for r in kept]
+    Vh = [[math.fsum(col) / math.fsum(den[r]) for col in num_v[r]] for r in kept]
+    return Kh, Vh
+
+
+@pytest.mark.parametrize("seed,T,b,d", [(0, 9, 4, 5), (1, 14, 3, 8), (2, 6, 5, 3), (3, 12, 1, 4)])
+def test_merge_matches_pure_python(seed, T, b, d):
+    rng = np.random.default_rng(100 + seed)
+    K, V = rng.standard_normal((T, d)), rng.standard_normal((T, d + 1))
+    I = np.sort(rng.choice(T, b, replace=False))
+    Kh, Vh, _, _ = ho.merge_final(K, V, I)
+    Kw, Vw = bf_merge(K.tolist(), V.tolist(), I)
+    assert np.allclose(Kh, Kw, rtol=1e-12, atol=1e-13) and np.allclose(Vh, Vw, rtol=1e-12, atol=1e-13)
+
+
+def test_merge_hand_computed_four_keys():
+    # kept rows 0 and 1; row 2 = (3, 4): cosine 0.6 to row 0 and 0.8 to row 1 -> merged into row 1 with weight 0.8;
+    # row 3 = (-1, 0): cosine -1 to row 0 and 0 to row 1 -> nearest is row 1, weight max(0, 0) = 0: contributes nothing
+    K = np.array([[1.0, 0.0], [0.0, 1.0], [3.0, 4.0], [-1.0, 0.0]])
+    V = np.array([[1.0, 2.0], [3.0, 4.0], [5.0, 6.0], [7.0, 8.0]])
+    Kh, Vh, nearest, weight = ho.merge_final(K, V, np.array([0, 1]))
+    assert list(nearest) == [1, 1] and np.allclose(weight, [0.8, 0.0])
+    assert np.allclose(Kh, [[1.0, 0.0], [(0 + 0.8 * 3) / 1.8, (1 + 0.8 * 4) / 1.8]])
+    assert np.allclose(Vh, [[1.0, 2.0], [(3 + 0.8 * 5) / 1.8, (4 + 0.8 * 6) / 1.8]])
+
+
+def test_merge_properties():
+    rng = np.random.default_rng(7)
+    T, d = 40, 6
+    K = rng.standard_normal((T, d))
+    I = np.sort(rng.choice(T, 11, replace=False))
+    # nothing evicted -> the kept rows come back untouched
+    Kh, Vh, nearest, weight = ho.merge_final(K, K * 2, np.arange(T))
+    assert np.array_equal(Kh, K) and np.array_equal(Vh, K * 2) and nearest.size == 0
+    # every merged row is a convex combination of original rows: with V = identity the merged V rows ARE the
+    # weights: non-negative, summing to 1, the kept row's own weight the largest possible share 1/(1+sum w)
+    Kh, Wh, nearest, weight = ho.merge_final(K, np.eye(T), I)
+    assert np.all(Wh >= 0) and np.allclose(Wh.sum(axis=1), 1.0)
+    evicted = np.setdiff1d(np.arange(T), I)
+    for pos, r in enumerate(I):
+        mine = evicted[nearest == pos]
+        assert np.allclose(Wh[pos, r], 1.0 / (1.0 + weight[nearest == pos].sum()))
+        assert np.allclose(Wh[pos, mine] * (1.0 + weight[nearest == pos].sum()), weight[nearest == pos])
+        others = np.setdiff1d(np.arange(T), np.concatenate([[r], mine]))
+        assert np.all(Wh[pos, others] == 0)                       # every evicted row goes to exactly one kept row
+    assert np.allclose(Wh.sum(axis=0)[evicted] > 0, weight > 0)
+    # constant values stay constant; keys and values use the same weights
+    _, Vc, _, _ = ho.merge_final(K, np.full((T, 3), 2.5), I)
+    assert np.allclose(Vc, 2.5)
+    Kh2, Vh2, _, _ = ho.merge_final(K, K, I)
+    assert np.allclose(Kh2, Vh2)
+    # each evicted row goes to its most similar kept row (cosine: rescaling a row changes nothing)
+    S = (K[evicted] / np.linalg.norm(K[evicted], axis=1, keepdims=True)) @ (K[I] / np.linalg.norm(K[I], axis=1, keepdims=True)).T
+    assert np.array_equal(nearest, S.argmax(axis=1)) and np.allclose(weight, np.maximum(S.max(axis=1), 0))
+    K_scaled = K.copy()
+    K_scaled[evicted[0]] *= 7.0
+    _, _, n2, w2 = ho.merge_final(K_scaled, K, I)
+    assert np.array_equal(n2, nearest) and np.allclose(w2, weight)
+    # an evicted copy of a kept row leaves that row as it is (similarity 1, weight 1, same vector)
+    K3, V3 = K.copy(), rng.standard_normal((T, d))
+    K3[evicted[3]], V3[evicted[3]] = K3[I[2]], V3[I[2]]
+    only = np.array([I[2], I[5]])
+    K4, V4 = K3[[I[2], I[5], evicted[3]]], V3[[I[2], I[5], evicted[3]]]
+    Kh4, Vh4, n4, w4 = ho.merge_final(K4, V4, np.array([0, 1]))
+    assert list(n4) == [0] and np.allclose(w4, [1.0]) and np.allclose(Kh4, K4[:2]) and np.allclose(Vh4, V4[:2])
+    assert only.size == 2
+    # a tie between two identical kept rows goes to the lower index
+    K5 = np.array([[1.0, 1.0], [1.0, 1.0], [2.0, 2.0]])
+    _, _, n5, _ = ho.merge_final(K5, K5, np.array([0, 1]))
+    assert list(n5) == [0]
+    # a row of zero norm is similar to nothing
+    K6 = np.array([[1.0, 0.0], [0.0, 0.0]])
+    Kh6, _, n6, w6 = ho.merge_final(K6, K6, np.array([0]))
+    assert np.allclose(w6, [0.0]) and np.allclose(Kh6, [[1.0, 0.0]])
+
+
+def test_merge_happens_only_for_contextual_heads_at_the_final_step():
+    steps = _tiny_schedule(5, sides=(1, 2, 3, 4), H=2)
+    types = np.array([ho.CONTEXTUAL, ho.STRUCTURAL])
+    budgets = [np.array([1 << 30, 1 << 30])] * 2 + [np.array([8, 12]), np.array([9, 25])]
+    n_init, scale = 5, 0.35
+    plain = ho.run_schedule(steps, types, budgets, n_init, scale, 8)
+    merged = ho.run_schedule(steps, types, budgets, n_init, scale, 8, final_merge=True)
+    for k in range(3):                                  # earlier steps: identical
+        for u in range(2):
+            assert np.array_equal(plain[k][u]["K"], merged[k][u]["K"]) and np.array_equal(plain[k][u]["O"], merged[k][u]["O"])
+    # last step: same kept set for both heads; the structural head is untouched, the contextual head holds merged rows
+    assert np.array_equal(plain[3][0]["I"], merged[3][0]["I"]) and np.array_equal(plain[3][0]["pos"], merged[3][0]["pos"])
+    assert np.array_equal(plain[3][1]["K"], merged[3][1]["K"]) and np.array_equal(plain[3][1]["O"], merged[3][1]["O"])
+    K_in = np.concatenate([plain[2][0]["K"], steps[3][1][0, 0]])
+    V_in = np.concatenate([plain[2][0]["V"], steps[3][2][0, 0]])
+    Kw, Vw = bf_merge(K_in.tolist(), V_in.tolist(), plain[3][0]["I"])
+    assert np.allclose(merged[3][0]["K"], Kw) and np.allclose(merged[3][0]["V"], Vw)
+    assert not np.allclose(merged[3][0]["K"], plain[3][0]["K"])
+    # and the step's attention runs over the merged rows (compression, merge included, precedes attention)
+    assert np.allclose(merged[3][0]["O"], ho.attention(steps[3][0][0, 0], np.array(Kw), np.array(Vw), scale))
