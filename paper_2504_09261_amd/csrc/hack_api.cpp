@@ -78,6 +78,7 @@ struct hack_ctx {
   int score_capacity = 0;        // bf16 path: score items one launch may hold (resident waves), default item size
   int score_capacity_large = 0;  // the same for the larger item size
   int split_max_items = 0;       // launches with at most this many 32-query attention items use the key-split kernel
+  int attn_kernel = 1;           // bf16 kernel of the 128-query items: 1 = deeper pipeline, 0 = plain (HACK_ATTN_PIPE=0)
   int64_t ws_stride = 0;
   int max_chunks = 0;
   // launch-table cache: tables keep their device address for the life of the context
@@ -406,6 +407,7 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (const char* v = std::getenv("HACK_SCORE_TEST_SKIP_PUBLISH")) ctx->skip_publish = std::atoi(v);
   if (const char* v = std::getenv("HACK_SCORE_MODE")) ctx->score_mode = std::atoi(v) == 1 ? HACK_SCORE_TWO_PASS : HACK_SCORE_FUSED;
   if (const char* v = std::getenv("HACK_ATTN_SPLIT_ITEMS")) ctx->split_max_items = std::atoi(v);   // tuning / test override
+  if (const char* v = std::getenv("HACK_ATTN_PIPE")) ctx->attn_kernel = std::max(0, std::min(4, std::atoi(v)));   // A/B and test override
   hipError_t e = hipSetDevice(cfg->device);
   const size_t n_ws = (size_t)cfg->max_units * ctx->ws_stride;
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->importance, n_ws * sizeof(float));
@@ -649,7 +651,7 @@ extern "C" hack_status hack_attn(hack_ctx* ctx, int32_t B, int32_t N_k, const vo
                       out);
   else
     launch_attn(s, ctx->cfg.dtype, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), (const AttnItem*)(dev + o_items),
-                (int)items.size(), tile, q, kv->k, kv->v, N_k, scale, out);
+                (int)items.size(), tile, q, kv->k, kv->v, N_k, scale, out, ctx->attn_kernel);
   HIP_TRY(ctx, hipGetLastError());
   return HACK_OK;
 }
@@ -835,7 +837,7 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
                       fuse_append ? 1 : 0, N_k, scale, out);
   else
     launch_attn(s, ctx->cfg.dtype, ctx->cfg.head_dim, ddev, (const AttnItem*)(dev + o_items), (int)items.size(), tile,
-                q, cache->k, cache->v, N_k, scale, out);
+                q, cache->k, cache->v, N_k, scale, out, ctx->attn_kernel);
   HIP_TRY(ctx, hipGetLastError());
 
   for (int u = 0; u < U; ++u) {

@@ -103,9 +103,12 @@ void launch_select(hipStream_t s, const UnitDesc* descs, const int32_t* list, in
 size_t select_lds_bytes(int max_t_in);
 
 // Attention of N_k queries per unit over rows [out_off, out_off + n_out).
+// bf16_kernel: which bf16 kernel serves the 128-query work items, 1 = the deeper
+// software pipeline (default), 0 = the plain one-block pipeline (kept for A/B timing
+// and as a second implementation the tests run over the same shapes).
 void launch_attn(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, const AttnItem* items,
                  int n_items, int q_tile_rows, const void* q, const void* k_cache,
-                 const void* v_cache, int N_k, float scale, void* out);
+                 const void* v_cache, int N_k, float scale, void* out, int bf16_kernel);
 // bf16 attention for steps with few queries: work item = (unit, tile of
 // attn_split_q_tile_rows() queries), keys split over the waves of a work-group.
 // fuse == 0: attends over rows [out_off, out_off + n_out) of k_cache / v_cache.

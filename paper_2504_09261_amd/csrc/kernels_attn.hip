@@ -458,7 +458,378 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
   }
 }
 
+
+// ---------------------------------------------------------------------------
+// bf16 MFMA path, deeper software pipeline (the kernel that serves the large steps)
+// ---------------------------------------------------------------------------
+// Same work item, operand layouts, swizzles and softmax as attn_mfma above; what
+// differs is what one stage holds.  Stage b (one barrier) is a single branch-free
+// region with three independent strands:
+//     S(b+1)   the 8 score MFMAs of the next block       (matrix core)
+//     PV(b-1)  O^T += V^T P^T of the previous block       (matrix core)
+//     softmax(b): exponentials, bf16 packing, row sum    (vector ALU)
+// so every MFMA of the loop has vector work of another block beside it and the LDS
+// reads of both products are issued ahead of their use.  The probabilities of block
+// b wait in registers for one stage; the check "did a probability leave the safe
+// range" (and the rare rescale that follows it) sits at the end of the stage, after
+// PV(b-1) has been added, so a rescale always meets accumulators that are complete
+// up to block b-1.
+// LDS: three slots per tensor.  K(j) is read in stage j-1, V(j) in stage j+1; stage
+// b issues the copies K(b+3) and V(b+1) right after its opening barrier, into the
+// slots of K(b) and V(b-2), which every wave finished reading in stage b-1.  Each
+// copy has two full stages to land; one s_waitcnt vmcnt(2 groups) + barrier per stage.
+// Scheduling hints for one pipelined stage: N times {one MFMA, VALU_PER vector ops,
+// up to two LDS reads while any are left}.
+template <int I, int N, int VALU_PER, int DS_LEFT>
+__device__ __forceinline__ void sched_interleave() {
+  if constexpr (I < N) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, VALU_PER, 0);
+    if constexpr (DS_LEFT >= 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    else if constexpr (DS_LEFT == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    sched_interleave<I + 1, N, VALU_PER, (DS_LEFT > 2 ? DS_LEFT - 2 : 0)>();
+  }
+}
+
+// MFMA cluster first (operand reads two ahead), vector work afterwards.
+template <int I, int N, int DS_LEFT>
+__device__ __forceinline__ void sched_cluster() {
+  if constexpr (I < N) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    if constexpr (DS_LEFT >= 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    else if constexpr (DS_LEFT == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    sched_cluster<I + 1, N, (DS_LEFT > 2 ? DS_LEFT - 2 : 0)>();
+  }
+}
+
+#ifdef HACK_ATTN_PROF
+__device__ long long g_attn_prof[4096 * 4 * 4];
+#endif
+
+// SCHED: how the three strands of a stage are laid out in the instruction stream
+//   0  every MFMA followed by a slice of the softmax arithmetic and the next operand reads
+//   1  the same, the wave at raised priority from the first to the last MFMA of the stage
+//   2  the 16 MFMAs as one cluster at raised priority, the softmax arithmetic after it at
+//      normal priority (two waves of a SIMD then tend to alternate: one on the matrix core,
+//      the other on the vector ALU)
+//   3  as 2 without the priority changes
+template <int D, int NW, int SCHED>
+__global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
+    const UnitDesc* __restrict__ descs, const AttnItem* __restrict__ items,
+    const __bf16* __restrict__ q, const __bf16* __restrict__ k_cache,
+    const __bf16* __restrict__ v_cache, int N_k, float scale,
+    __bf16* __restrict__ out) {
+  constexpr int KK = D / 16;        // MFMA steps over head_dim for S^T
+  constexpr int MB = D / 32;        // 32-row blocks of O^T
+  constexpr int CPR = D / 8;        // 16-byte chunks per row
+  constexpr int RPI = 64 / CPR;     // block rows covered by one wave-wide copy instruction
+  constexpr int IPW = (kKB / RPI) / NW;  // copy instructions per wave, block and tensor
+  constexpr int BLK = kKB * D;      // elements per block and tensor
+  constexpr int NS = 3;             // ring slots per tensor
+  static_assert(IPW >= 1, "a block must give every wave at least one copy instruction");
+  static_assert(KK == 2 * MB, "as many score MFMAs as PV MFMAs per block");
+
+  const AttnItem it = items[blockIdx.x];
+  if (it.desc < 0) return;
+  const UnitDesc d = descs[it.desc];
+  const int len = d.n_out;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int col = lane & 31, half = lane >> 5;
+
+  __shared__ __attribute__((aligned(1024))) __bf16 Ks[NS][BLK];
+  __shared__ __attribute__((aligned(1024))) __bf16 Vs[NS][BLK];
+
+  const __bf16* kg = k_cache + d.out_off * D;
+  const __bf16* vg = v_cache + d.out_off * D;
+  const int n_blocks = (len + kKB - 1) / kKB;
+  const int n_full = len / kKB;
+
+  unsigned k_src[IPW], v_src[IPW];
+#pragma unroll
+  for (int i = 0; i < IPW; ++i) {
+    const int r = (w + i * NW) * RPI + lane / CPR, c = lane % CPR;
+    k_src[i] = (unsigned)(r * D + ((c ^ swz_k<D>(r)) & (CPR - 1)) * 8) * 2u;
+    v_src[i] = (unsigned)(r * D + ((c ^ swz_v<D>(r)) & (CPR - 1)) * 8) * 2u;
+  }
+  const unsigned ks_lds = lds_addr_of(&Ks[0][0]), vs_lds = lds_addr_of(&Vs[0][0]);
+  // Copy of block blk of one tensor into ring slot `slot`.  Rows past the end of a
+  // ragged last block repeat the last valid row (finite data); their scores are
+  // masked to -inf, so their probabilities are exactly 0.
+  auto issue_one = [&](const __bf16* g, const unsigned (&src)[IPW], unsigned lds, bool is_v, int blk, int slot, bool full) {
+    const int t0 = blk * kKB;
+    const __bf16* gb = g + (int64_t)t0 * D;
+    if (full || t0 + kKB <= len) {
+#pragma unroll
+      for (int i = 0; i < IPW; ++i)
+        load_to_lds(gb, src[i], lds + (unsigned)((slot * BLK + (w + i * NW) * 512) * 2));
+    } else {
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        const int r = (w + i * NW) * RPI + lane / CPR, c = lane % CPR;
+        const int rc = min(r, len - 1 - t0);
+        const int f = is_v ? swz_v<D>(r) : swz_k<D>(r);
+        load_to_lds(gb, (unsigned)(rc * D + ((c ^ f) & (CPR - 1)) * 8) * 2u,
+                    lds + (unsigned)((slot * BLK + (w + i * NW) * 512) * 2));
+      }
+    }
+  };
+  auto issue_k = [&](int blk, int slot, bool full = false) { issue_one(kg, k_src, ks_lds, false, blk, slot, full); };
+  auto issue_v = [&](int blk, int slot, bool full = false) { issue_one(vg, v_src, vs_lds, true, blk, slot, full); };
+
+  issue_k(0, 0);
+  if (n_blocks > 1) issue_k(1, 1);
+  if (n_blocks > 2) issue_k(2, 2);
+  issue_v(0, 0);
+
+  // Q fragments (B operand of S^T = K Q^T): query col, head-dim slice [16kk + 8h, +8).
+  const int q0 = it.q_tile * (NW * 32) + w * 32;
+  bf16x8 qf[KK];
+  {
+    const int qi = min(q0 + col, N_k - 1);
+    const __bf16* qrow = q + ((int64_t)d.unit * N_k + qi) * D;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) qf[kk] = *reinterpret_cast<const bf16x8*>(qrow + 16 * kk + 8 * half);
+    // Consumed here so that their loads are waited for before the main loop (a vmcnt
+    // wait inside the loop would also drain the block copies meant to stay in flight).
+    // The copies issued above are older than these loads and have landed with them.
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) asm volatile("" ::"v"(qf[kk]));
+  }
+
+  floatx16 o[MB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[mb][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c2 = scale * kLog2eF;
+  float mc = -INFINITY;   // m_run * c2
+
+  int k_off[KK];           // K operand: row col, chunk 2kk + half
+#pragma unroll
+  for (int kk = 0; kk < KK; ++kk) k_off[kk] = col * D + (((2 * kk + half) ^ swz_k<D>(col)) & (CPR - 1)) * 8;
+  const int g = lane >> 4, e = (lane >> 2) & 3, qd = lane & 3;
+  int v_off[MB];           // V^T operand: row 4 half + e (+16 sg, +8), head-dim 32mb + 16(g&1) + 4qd
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+    v_off[mb] = (4 * half + e) * D + (((4 * mb + 2 * (g & 1) + (qd >> 1)) ^ swz_v<D>(e)) & (CPR - 1)) * 8 + 4 * (qd & 1);
+
+  const bf16x2 ones2 = {(__bf16)1.0f, (__bf16)1.0f};
+
+  auto mask_tail = [&](floatx16& sc, int b) {
+    if ((b + 1) * kKB > len) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = b * kKB + 8 * (r >> 2) + 4 * half + (r & 3);
+        if (key >= len) sc[r] = -INFINITY;
+      }
+    }
+  };
+  auto probs = [&](const floatx16& sc, bf16x8 (&pf)[2]) -> float {
+    float psum = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) pf[r >> 3][r & 7] = (__bf16)__builtin_amdgcn_exp2f(fmaf(sc[r], c2, -mc));
+#pragma unroll
+    for (int r = 0; r < 16; r += 2) {
+      const bf16x2 pr = {pf[r >> 3][r & 7], pf[r >> 3][(r & 7) + 1]};
+      psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones2, psum, false);
+    }
+    return psum;
+  };
+  auto rescale = [&](const floatx16& sc, bf16x8 (&pf)[2]) -> float {
+    float mx = sc[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sc[r]);
+    mx = pair_max(mx);
+    const float m_new = fmaxf(m_run, mx);   // finite: the block holds a valid key
+    const float a = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+    l_run *= a;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[mb][r] *= a;
+    m_run = m_new;
+    mc = m_new * c2;
+    return probs(sc, pf);
+  };
+  auto k_frag = [&](const __bf16* Kt, int kk) -> bf16x8 { return *reinterpret_cast<const bf16x8*>(&Kt[k_off[kk]]); };
+  auto v_frag = [&](const __bf16* Vt, int i) -> bf16x8 {   // PV MFMA i: key group sg = i / MB, head-dim block mb = i % MB
+    const __bf16* vp = &Vt[16 * (i / MB) * D + v_off[i % MB]];
+    const bf16x4 v0 = lds_read_tr(vp);
+    const bf16x4 v1 = lds_read_tr(vp + 8 * D);
+    bf16x8 vf;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      vf[j] = v0[j];
+      vf[4 + j] = v1[j];
+    }
+    return vf;
+  };
+
+  bf16x8 pp[2];   // probabilities of the previous block, waiting for their PV product
+#ifdef HACK_ATTN_PROF
+  long long prof_dma = 0, prof_bar = 0, prof_work = 0;
+  const long long prof_start = clock64();
+#endif
+
+  // Stage b, ring slot S = b % 3 (compile time).  On entry sc = scores of block b and
+  // pp = probabilities of block b-1; on exit sc = scores of block b+1, pp = those of block b.
+  // FIRST: b == 0 (no previous block).  LAST: block b is the unit's last (no next scores).
+  // STEADY: every block this stage touches exists and is full, so copies, waits and
+  // masks need no tests.
+  auto stage = [&](auto slot_tag, auto first_tag, auto last_tag, auto steady_tag, int b, floatx16& sc) {
+    constexpr int S = decltype(slot_tag)::value;
+    constexpr bool FIRST = decltype(first_tag)::value;
+    constexpr bool LAST = decltype(last_tag)::value;
+    constexpr bool STEADY = decltype(steady_tag)::value;
+#ifdef HACK_ATTN_PROF
+    const long long pt0 = clock64();
+#endif
+    // K(b+1) and V(b-1) have landed: everything but the two copy groups issued one stage ago
+    if (STEADY) dma_wait_but<2 * IPW>();
+    else dma_wait_but<0>();
+#ifdef HACK_ATTN_PROF
+    const long long pt1 = clock64();
+#endif
+    __syncthreads();   // both are visible to every wave; the slots of K(b) and V(b-2) are free
+#ifdef HACK_ATTN_PROF
+    const long long pt2 = clock64();
+#endif
+    if (STEADY || b + 3 < n_blocks) issue_k(b + 3, S, STEADY);
+    if (STEADY || b + 1 < n_blocks) issue_v(b + 1, (S + 1) % NS, STEADY);
+    __builtin_amdgcn_sched_barrier(0);
+    if (SCHED == 1 || SCHED == 2) {
+      __builtin_amdgcn_s_setprio(2);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    const __bf16* Kt = &Ks[(S + 1) % NS][0];
+    const __bf16* Vt = &Vs[(S + 2) % NS][0];
+    floatx16 sn;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sn[r] = 0.f;
+#pragma unroll
+    for (int i = 0; i < KK; ++i) {
+      if (!LAST) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(Kt, i), qf[i], sn, 0, 0, 0);
+      if (!FIRST) o[i % MB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag(Vt, i), pp[i / MB], o[i % MB], 0, 0, 0);
+    }
+    bf16x8 pf[2];
+    float psum;
+    if constexpr (SCHED >= 2) {
+      // all MFMAs of the stage, then the vector work
+      __builtin_amdgcn_sched_barrier(0);
+      if (SCHED == 2) __builtin_amdgcn_s_setprio(0);
+      psum = probs(sc, pf);
+    } else {
+      psum = probs(sc, pf);
+      // a few operand reads ahead, then per MFMA a slice of the softmax arithmetic and the next reads
+      constexpr int N_MFMA = (LAST ? 0 : KK) + (FIRST ? 0 : KK);
+      constexpr int N_DS = (LAST ? 0 : KK) + (FIRST ? 0 : 2 * KK);
+      constexpr int AHEAD = N_DS < 6 ? N_DS : 6;
+      constexpr int VALU_PER = N_MFMA ? (48 + N_MFMA - 1) / N_MFMA : 0;
+      if constexpr (N_MFMA > 0) {
+        __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
+        sched_interleave<0, N_MFMA, VALU_PER, N_DS - AHEAD>();
+      }
+      if (SCHED == 1) {
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(0);
+      }
+    }
+    if (!STEADY && !LAST) mask_tail(sn, b + 1);
+    if (__any(!(psum < kRescaleAbove))) psum = rescale(sc, pf);
+    l_run += psum;
+    pp[0] = pf[0];
+    pp[1] = pf[1];
+    if (!LAST) sc = sn;
+#ifdef HACK_ATTN_PROF
+    asm volatile("" ::"v"(o[0]), "v"(o[MB - 1]), "v"(sc));
+    const long long pt3 = clock64();
+    prof_dma += pt1 - pt0;
+    prof_bar += pt2 - pt1;
+    prof_work += pt3 - pt2;
+#endif
+  };
+
+  using R0 = std::integral_constant<int, 0>;
+  using R1 = std::integral_constant<int, 1>;
+  using R2 = std::integral_constant<int, 2>;
+  using No = std::false_type;
+  using Yes = std::true_type;
+
+  // block 0 has landed (see the Q fragments above) -> its scores
+  dma_wait_but<0>();
+  __syncthreads();
+  floatx16 sc;
+  {
+    const __bf16* Kt = &Ks[0][0];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sc[r] = 0.f;
+#pragma unroll
+    for (int kk = 0; kk < KK; ++kk) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(k_frag(Kt, kk), qf[kk], sc, 0, 0, 0);
+  }
+  mask_tail(sc, 0);
+
+  // stage 0 on its own (no previous block), then the steady loop: stages whose blocks b-1 .. b+3 all exist and are full
+  if (n_blocks == 1) stage(R0{}, Yes{}, Yes{}, No{}, 0, sc);
+  else stage(R0{}, Yes{}, No{}, No{}, 0, sc);
+  int b = 1;
+  for (; b + 5 < n_full; b += 3) {
+    stage(R1{}, No{}, No{}, Yes{}, b, sc);
+    stage(R2{}, No{}, No{}, Yes{}, b + 1, sc);
+    stage(R0{}, No{}, No{}, Yes{}, b + 2, sc);
+  }
+  // the remaining blocks, one stage at a time (b % 3 == 1 here)
+  for (; b < n_blocks; ++b) {
+    const bool last = (b + 1 == n_blocks);
+    switch (b % 3) {
+      case 0: if (last) stage(R0{}, No{}, Yes{}, No{}, b, sc); else stage(R0{}, No{}, No{}, No{}, b, sc); break;
+      case 1: if (last) stage(R1{}, No{}, Yes{}, No{}, b, sc); else stage(R1{}, No{}, No{}, No{}, b, sc); break;
+      default: if (last) stage(R2{}, No{}, Yes{}, No{}, b, sc); else stage(R2{}, No{}, No{}, No{}, b, sc); break;
+    }
+  }
+  // PV of the last block
+  dma_wait_but<0>();
+  __syncthreads();
+  {
+    const __bf16* Vt = &Vs[(n_blocks - 1) % NS][0];
+#pragma unroll
+    for (int i = 0; i < KK; ++i)
+      o[i % MB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag(Vt, i), pp[i / MB], o[i % MB], 0, 0, 0);
+  }
+
+  // ---- normalise and store: lane holds query col, head-dim rows 32mb + 8(r/4) + 4h + r%4 ----
+  const float l = pair_sum(l_run);
+  const float inv = 1.f / l;
+  const int qi = q0 + col;
+  if (qi < N_k) {
+    __bf16* orow = out + ((int64_t)d.unit * N_k + qi) * D;
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4) {
+        bf16x4 pk;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) pk[i] = (__bf16)(o[mb][4 * r4 + i] * inv);
+        *reinterpret_cast<bf16x4*>(orow + 32 * mb + 8 * r4 + 4 * half) = pk;
+      }
+    }
+  }
+#ifdef HACK_ATTN_PROF
+  if (lane == 0 && blockIdx.x < 4096) {
+    long long* p = g_attn_prof + ((size_t)blockIdx.x * 4 + w) * 4;
+    p[0] = prof_dma; p[1] = prof_bar; p[2] = prof_work; p[3] = clock64() - prof_start;
+  }
+#endif
+}
+
 }  // namespace
+
+#ifdef HACK_ATTN_PROF
+extern "C" int hack_debug_attn_prof(long long* dst, size_t n) {
+  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_attn_prof), n * sizeof(long long));
+}
+#endif
 
 // Queries per work item.
 int attn_q_tile_rows(int dtype, int head_dim, int n_units, int N_k) {
@@ -469,15 +840,24 @@ int attn_q_tile_rows(int dtype, int head_dim, int n_units, int N_k) {
 template <int D, int NW>
 static void launch_mfma_t(hipStream_t s, const UnitDesc* descs, const AttnItem* items, int n_items,
                           const void* q, const void* k_cache, const void* v_cache, int N_k,
-                          float scale, void* out) {
+                          float scale, void* out, int kernel) {
   typedef __bf16 T;
-  hipLaunchKernelGGL((attn_mfma<D, NW>), dim3(n_items), dim3(64 * NW), 0, s, descs, items,
-                     (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out);
+#define HACK_PIPE(SCHED_)                                                                                  \
+  hipLaunchKernelGGL((attn_pipe<D, NW, SCHED_>), dim3(n_items), dim3(64 * NW), 0, s, descs, items, \
+                     (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out)
+  if (kernel == 1) HACK_PIPE(0);
+  else if (kernel == 2) HACK_PIPE(1);
+  else if (kernel == 3) HACK_PIPE(2);
+  else if (kernel == 4) HACK_PIPE(3);
+#undef HACK_PIPE
+  else
+    hipLaunchKernelGGL((attn_mfma<D, NW>), dim3(n_items), dim3(64 * NW), 0, s, descs, items,
+                       (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out);
 }
 
 void launch_attn(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, const AttnItem* items,
                  int n_items, int q_tile_rows, const void* q, const void* k_cache,
-                 const void* v_cache, int N_k, float scale, void* out) {
+                 const void* v_cache, int N_k, float scale, void* out, int bf16_kernel) {
   if (n_items <= 0) return;
   (void)q_tile_rows;
   if (dtype == 1) {
@@ -491,8 +871,8 @@ void launch_attn(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, 
                          (float*)out);
     return;
   }
-  if (head_dim == 64) launch_mfma_t<64, 4>(s, descs, items, n_items, q, k_cache, v_cache, N_k, scale, out);
-  else launch_mfma_t<128, 4>(s, descs, items, n_items, q, k_cache, v_cache, N_k, scale, out);
+  if (head_dim == 64) launch_mfma_t<64, 4>(s, descs, items, n_items, q, k_cache, v_cache, N_k, scale, out, bf16_kernel);
+  else launch_mfma_t<128, 4>(s, descs, items, n_items, q, k_cache, v_cache, N_k, scale, out, bf16_kernel);
 }
 
 }  // namespace hack

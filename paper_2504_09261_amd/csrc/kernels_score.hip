@@ -438,7 +438,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
     if (col == 0) red[c_row(r, half)] = l;
   }
   __syncthreads();
-  if (MODE != kScoreWrite && w == 0 && lane < kMaxObs && (int)blockIdx.x != skip_publish) {
+  if (MODE != kScoreWrite && w == 0 && lane < kMaxObs && (MODE != kScoreFused || (int)blockIdx.x != skip_publish)) {
     double tot = 0.0;
 #pragma unroll
     for (int k = 0; k < 4; ++k) tot += reinterpret_cast<const double*>(&tiles[k][0][0])[lane];

@@ -57,24 +57,28 @@ def build_cache(rows_per_unit, d, dtype, pad_rows=0, fill=None):
 
 def make_hack(cfg_or_none=None, *, heads=None, head_dim=None, dtype=None, max_units=None, max_cache_len=None,
               max_queries=None, n_obs=32, attention=None) -> Hack:
-    """attention: None = the library's own choice between its two bf16 attention kernels per launch;
-    "split" / "tile128" = force the key-split (32-query items) or the 128-query-tile kernel for every
-    launch of this context (the library reads the override when the context is created)."""
+    """attention: None = the library's own choice between its bf16 attention kernels per launch;
+    "split" / "tile128" = force the key-split (32-query items) or the 128-query-tile kernel (the
+    deeper software pipeline) for every launch of this context; "tile128_plain" = 128-query tiles
+    through the plain one-block pipeline (the library reads the overrides when the context is created)."""
     import os
-    saved = os.environ.get("HACK_ATTN_SPLIT_ITEMS")
+    env = {}
     if attention is not None:
-        os.environ["HACK_ATTN_SPLIT_ITEMS"] = {"split": "2000000000", "tile128": "0"}[attention]
+        env["HACK_ATTN_SPLIT_ITEMS"] = {"split": "2000000000", "tile128": "0", "tile128_plain": "0"}[attention]
+        env["HACK_ATTN_PIPE"] = "0" if attention == "tile128_plain" else "1"
+    saved = {k: os.environ.get(k) for k in env}
+    os.environ.update(env)
     try:
         if cfg_or_none is not None:
             c = cfg_or_none
             return Hack(c.heads, c.head_dim, c.dtype, c.n_units, c.T_K, max(c.N), c.n_obs)
         return Hack(heads, head_dim, dtype, max_units, max_cache_len, max_queries, n_obs)
     finally:
-        if attention is not None:
-            if saved is None:
-                del os.environ["HACK_ATTN_SPLIT_ITEMS"]
+        for k, v in saved.items():
+            if v is None:
+                del os.environ[k]
             else:
-                os.environ["HACK_ATTN_SPLIT_ITEMS"] = saved
+                os.environ[k] = v
 
 
 # the verdict rules live with the oracle-side checker (pure numpy)

@@ -325,6 +325,11 @@ def test_score_cache_only_custom_rows_and_inactive_units():
     ("bf16", 128, 1, [1, 5, 21, 57, 121, 265, 64, 32], 2e-2, "split"),
     ("bf16", 64, 33, [3, 31, 32, 96, 97, 160, 2000, 129], 2e-2, "split"),
     ("bf16", 128, 300, [1, 2, 63, 64, 65, 1943, 127, 700], 2e-2, None),
+    ("bf16", 128, 300, [1, 2, 63, 64, 65, 1943, 127, 700], 2e-2, "tile128_plain"),
+    ("bf16", 64, 100, [102, 306, 1, 33, 562, 91, 128, 129], 2e-2, "tile128_plain"),
+    ("bf16", 128, 130, [96, 97, 192, 193, 224, 225, 256, 289], 2e-2, "tile128"),      # 3 .. 10 key blocks: every
+    ("bf16", 64, 130, [96, 97, 192, 193, 224, 225, 256, 289], 2e-2, "tile128"),       # way in and out of the steady loop
+    ("bf16", 128, 130, [320, 321, 351, 352, 353, 384, 416, 449], 2e-2, "tile128"),
     ("f32", 64, 100, [102, 306, 1, 33, 562, 91, 128, 129], 1e-4, None),
     ("f32", 128, 70, [1, 2, 63, 64, 65, 300, 127, 31], 1e-4, None),
 ])
@@ -413,6 +418,12 @@ def test_score_give_up_is_contained_reported_and_recovered(monkeypatch):
     scale = 0.05
     imp1 = torch.full((H, 8192), -1.0, device=u.DEV)
     imp2 = torch.full((H, 8192), -1.0, device=u.DEV)
+    # a few milliseconds of other work first, so that both score calls are queued before the first one runs
+    # (the host looks at the fault word at every entry)
+    big = torch.randn((8192, 8192), device=u.DEV, dtype=torch.bfloat16)
+    torch.cuda.synchronize()
+    for _ in range(8):
+        big = (big @ big).clamp_(-1, 1)
     hk.score(qd, cin, scale, imp1)           # one unit of this launch never gets all its sums
     hk.score(qd, cin, scale, imp2)           # queued behind it: must leave without reading the slots
     torch.cuda.synchronize()
