@@ -153,6 +153,26 @@ hack_status hack_score(hack_ctx* ctx, int32_t B, int32_t N_k, const void* q,
                        const uint8_t* active, float* importance,
                        int64_t imp_stride, hack_stream stream);
 
+/* hack_score for callers that cannot allocate: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * importance bit for bit (the two-pass form: no in-kernel waits), but every
+ * scratch buffer of the kernels (work items, q-row table, row-sum exchange
+ * slots) lives in a fixed device array of the library (about 1.6 MB per GPU, held
+ * until the process ends) and the work items are planned by a kernel from by-value
+ * arguments, so the call performs no allocation of any kind and no host-to-device
+ * copy.  Limits: bf16 contexts (HACK_EUNSUPPORTED otherwise); at most 64
+ * scored units per call (HACK_ECAPACITY beyond; use `active` to score a
+ * larger batch in slices).  The array keeps no state between calls (every word
+ * a call reads it has written itself), but all calls on one GPU share it:
+ * calls that overlap in time on the same GPU, on whatever stream or context,
+ * race on it; issue them on one stream or order them with events.
+ * Other errors as hack_score. */
+hack_status hack_score_static(hack_ctx* ctx, int32_t B, int32_t N_k, const void* q,
+                              const int32_t* q_idx, int32_t n_obs, float scale,
+                              const hack_cache* in, const void* k_new,
+                              const uint8_t* active, float* importance,
+                              int64_t imp_stride, hack_stream stream);
+
 /* ---- a2: budgeted selection per head class -----------------------------
  * Sec. 4.4, f_C and f_S.  For unit u with T = t_in[u], b = min(budget[u], T):
  *   contextual: the b keys of largest importance;

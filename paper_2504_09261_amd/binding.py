@@ -23,7 +23,7 @@ EXPORTS = [
     "hack_score", "hack_select", "hack_compact", "hack_attn", "hack_attn_variant",
     "hack_kvcache_rows_required", "hack_kvcache_create", "hack_kvcache_destroy",
     "hack_kvcache_reset", "hack_kvcache_view", "hack_step", "hack_head_variance",
-    "hack_set_score_mode", "hack_get_score_mode",
+    "hack_set_score_mode", "hack_get_score_mode", "hack_score_static",
 ]
 
 
@@ -74,6 +74,7 @@ def load_library() -> C.CDLL:
     lib.hack_get_score_mode.argtypes = [vp]
     lib.hack_get_score_mode.restype = i32
     lib.hack_score.argtypes = [vp, i32, i32, vp, pi32, i32, f32, pcache, vp, pu8, vp, i64, vp]
+    lib.hack_score_static.argtypes = [vp, i32, i32, vp, pi32, i32, f32, pcache, vp, pu8, vp, i64, vp]
     lib.hack_select.argtypes = [vp, i32, vp, i64, pi32, pu8, pi32, i32, i32, vp, i64, pi32, vp]
     lib.hack_compact.argtypes = [vp, i32, i32, pcache, vp, vp, i32, vp, i64, pcache, vp]
     lib.hack_attn.argtypes = [vp, i32, i32, vp, pcache, f32, vp, vp]
@@ -238,6 +239,18 @@ class Hack:
         self._check(self.lib.hack_score(self.ctx, B, Nk, _dev(q), _p(qi, C.c_int32), n_obs, scale, C.byref(cs),
                                         _dev(k_new), _p(act, C.c_uint8), _dev(importance),
                                         importance.stride(0), _stream()))
+
+    def score_static(self, q, cache: Cache, scale: float, importance, k_new=None, q_idx=None,
+                     n_obs: Optional[int] = None, active=None):
+        """hack_score with all kernel scratch in the library's fixed device array (allocates nothing)."""
+        B, H, Nk, d = q.shape
+        n_obs = min(32, Nk) if n_obs is None else n_obs
+        qi = None if q_idx is None else _i32(q_idx)
+        act = None if active is None else _u8(active)
+        cs = cache.struct()
+        self._check(self.lib.hack_score_static(self.ctx, B, Nk, _dev(q), _p(qi, C.c_int32), n_obs, scale, C.byref(cs),
+                                               _dev(k_new), _p(act, C.c_uint8), _dev(importance),
+                                               importance.stride(0), _stream()))
 
     # ---- a2 ----
     def select(self, B: int, importance, t_in, head_type, budget, n_init: int, n_recent: int, kept_idx) -> np.ndarray:

@@ -431,6 +431,7 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
     ctx->tables = new (std::nothrow) TableCache<HipTableBackend>(HipTableBackend{}, kTableChunkBytes, kTableLimitBytes);
     if (!ctx->tables || !ctx->tables->reserve_first_chunk()) e = hipErrorOutOfMemory;
   }
+  if (e == hipSuccess) e = score_static_setup(cfg->device);   // device address of the library's fixed scratch array
   if (e == hipSuccess && cfg->dtype == HACK_BF16) {
     // a unit's score items wait for each other inside one launch, so a launch may
     // hold at most as many items as the device keeps resident at once
@@ -514,6 +515,46 @@ extern "C" hack_status hack_score(hack_ctx* ctx, int32_t B, int32_t N_k, const v
             (const ScoreItem*)(dev + o_sit), item_keys, groups, q, (const int32_t*)(dev + o_rows), n_obs, N_k, scale, in->k, k_new,
             importance, imp_stride);
   HIP_TRY(ctx, hipGetLastError());
+  return HACK_OK;
+}
+
+// The same call for callers that cannot allocate (see hack.h): scratch in the library's fixed device array.
+extern "C" hack_status hack_score_static(hack_ctx* ctx, int32_t B, int32_t N_k, const void* q, const int32_t* q_idx,
+                                         int32_t n_obs, float scale, const hack_cache* in, const void* k_new,
+                                         const uint8_t* active, float* importance, int64_t imp_stride,
+                                         hack_stream stream) {
+  hack_status st = check_common(ctx, B, N_k, true);
+  if (st != HACK_OK) return st;
+  if (ctx->cfg.dtype != HACK_BF16) return fail(ctx, HACK_EUNSUPPORTED, "hack_score_static is implemented for bf16 contexts");
+  const int U = B * ctx->cfg.heads;
+  if (!q || !importance) return fail(ctx, HACK_EINVAL, "q and importance must not be NULL");
+  if (!aligned16(q) || (k_new && !aligned16(k_new))) return fail(ctx, HACK_EINVAL, "q/k_new must be 16-byte aligned");
+  if (n_obs < 1 || n_obs > ctx->cfg.n_obs || n_obs > N_k)
+    return fail(ctx, HACK_EINVAL, "n_obs = %d outside [1, min(%d, N_k = %d)]", n_obs, ctx->cfg.n_obs, N_k);
+  if (!scale_ok(scale)) return fail(ctx, HACK_EINVAL, "scale must be finite and > 0");
+  if (q_idx)
+    for (int i = 0; i < n_obs; ++i)
+      if (q_idx[i] < 0 || q_idx[i] >= N_k) return fail(ctx, HACK_EINVAL, "q_idx[%d] = %d outside [0, %d)", i, q_idx[i], N_k);
+  if ((st = check_cache(ctx, in, U, "in", false)) != HACK_OK) return st;
+  StaticScorePlan plan{};
+  plan.n_new = k_new ? N_k : 0;
+  for (int u = 0; u < U; ++u) {
+    if (active && !active[u]) continue;
+    const int64_t T = (int64_t)in->len[u] + plan.n_new;
+    if (T < 1) return fail(ctx, HACK_EINVAL, "unit %d has no keys to score", u);
+    if (T > ctx->cfg.max_cache_len) return fail(ctx, HACK_ECAPACITY, "unit %d: T_in = %lld exceeds max_cache_len %d", u, (long long)T, ctx->cfg.max_cache_len);
+    if (T > imp_stride) return fail(ctx, HACK_ECAPACITY, "imp_stride %lld < T_in %lld of unit %d", (long long)imp_stride, (long long)T, u);
+    if (plan.n_units == kStaticUnitsMax)
+      return fail(ctx, HACK_ECAPACITY, "hack_score_static scores at most %d units per call", kStaticUnitsMax);
+    plan.in_off[plan.n_units] = in->off[u];
+    plan.len_in[plan.n_units] = in->len[u];
+    plan.unit[plan.n_units] = u;
+    ++plan.n_units;
+  }
+  if (plan.n_units == 0) return HACK_OK;
+  fill_q_rows(q_idx, n_obs, N_k, plan.q_rows);
+  HIP_TRY(ctx, launch_score_static(static_cast<hipStream_t>(stream), ctx->cfg.device, ctx->cfg.head_dim, plan, q, n_obs, N_k, scale,
+                                   in->k, k_new, importance, imp_stride, ctx->fault));
   return HACK_OK;
 }
 

@@ -89,6 +89,25 @@ void launch_score_fused(hipStream_t s, int head_dim, int item_keys, bool two_pas
                         const void* k_new, unsigned long long* slots, int slot_groups, unsigned* counters,
                         float* importance, int64_t imp_stride, int* fault, int spin_limit, const unsigned* abort_flag,
                         int skip_publish);
+// The same importance (bf16, two-pass form) with all scratch in a fixed device array of the
+// library instead of context memory; no allocation, no host-to-device copy.  At most
+// kStaticUnitsMax units per call; the plan travels by value as a kernel argument.
+constexpr int kStaticUnitsMax = 64;
+struct StaticScorePlan {
+  int64_t in_off[kStaticUnitsMax];   // first cached row of each planned unit
+  int32_t len_in[kStaticUnitsMax];   // cached rows
+  int32_t unit[kStaticUnitsMax];     // u = b*H + h
+  int32_t q_rows[kMaxObs];
+  int32_t n_units;
+  int32_t n_new;                     // rows of k_new that follow the cached ones (0 or N_k)
+};
+int score_static_units_max();
+size_t score_static_scratch_bytes();
+int score_static_item_count(const StaticScorePlan& plan);
+hipError_t score_static_setup(int device);   // once per device: finds the device address of the array
+hipError_t launch_score_static(hipStream_t s, int device, int head_dim, const StaticScorePlan& plan, const void* q, int n_obs,
+                               int N_k, float scale, const void* k_cache, const void* k_new, float* importance,
+                               int64_t imp_stride, int* fault);
 // fp32: two passes over (chunk of 256 keys, listed unit); list[n_list] indexes
 // descs; stats is a workspace of n_list * ceil(max_t_in / 256) * 64 doubles.
 void launch_score_generic(hipStream_t s, int head_dim, const UnitDesc* descs, const int32_t* list, int n_list,

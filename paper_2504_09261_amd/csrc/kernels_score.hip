@@ -22,6 +22,8 @@
 // ALU is spent on accuracy: logits are accumulated in fp64 and the exponential
 // is range-reduced exactly, which keeps float32 importance within a few ulp of
 // the exact value; the ranking that follows is decided on those float32 numbers.
+#include <mutex>
+
 #include "hack_internal.h"
 
 namespace hack {
@@ -604,6 +606,98 @@ void launch_score_fused(hipStream_t s, int head_dim, int item_keys, bool two_pas
     else HACK_SCORE_CALL(128, 4);
   }
 #undef HACK_SCORE_CALL
+}
+
+// ---------------------------------------------------------------------------
+// hack_score_static: the same importance with every scratch buffer in a fixed
+// device array of this library, for callers that must not allocate
+// ---------------------------------------------------------------------------
+// The score kernels' scratch (work items, q-row table, row-sum exchange slots) lives in
+// a file-scope device array instead of context memory; the work items are written by a
+// small planning kernel from by-value arguments, so nothing is copied from the host.
+// The array is one per GPU and shared by every call on that GPU.
+namespace {
+
+constexpr int kStaticItemsMax = kStaticUnitsMax * 4 * kMaxGroups;   // 4 items per work-group, kMaxGroups work-groups per unit
+struct StaticScratch {
+  ScoreItem items[kStaticItemsMax];                                        // 512 KiB
+  unsigned long long slots[(size_t)kStaticUnitsMax * kMaxGroups * kMaxObs]; // 1 MiB
+  int32_t q_rows[kMaxObs];
+  unsigned counters[2 * kStaticUnitsMax + 64];                             // unused by the two-pass form; abort word last
+};
+static __device__ __align__(256) unsigned char scratch[sizeof(StaticScratch)];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+StaticScratch* g_scratch_ptr[kMaxDevices] = {};   // device address of `scratch` on each GPU (its name is not one in host code)
+
+// Writes the work items of the planned units (4 * wgs items per unit, in caller order) and the
+// q-row table.  One work-group.
+__global__ __launch_bounds__(256) void score_static_plan(StaticScorePlan plan, ScoreItem* __restrict__ items,
+                                                          int32_t* __restrict__ q_rows) {
+  __shared__ int first[kStaticUnitsMax + 1];
+  if (threadIdx.x == 0) {
+    int n = 0;
+    for (int i = 0; i < plan.n_units; ++i) {
+      first[i] = n;
+      const int t_in = plan.len_in[i] + plan.n_new;
+      n += 4 * (((t_in + kItemKeys - 1) / kItemKeys + 3) / 4);
+    }
+    first[plan.n_units] = n;
+  }
+  if (threadIdx.x < kMaxObs) q_rows[threadIdx.x] = plan.q_rows[threadIdx.x];
+  __syncthreads();
+  for (int i = 0; i < plan.n_units; ++i) {
+    const int n = first[i + 1] - first[i];
+    const int t_in = plan.len_in[i] + plan.n_new;
+    for (int c = threadIdx.x; c < n; c += blockDim.x)
+      items[first[i] + c] = ScoreItem{plan.in_off[i], plan.unit[i], plan.len_in[i], t_in, c, i, n / 4};
+  }
+}
+
+}  // namespace
+
+int score_static_units_max() { return kStaticUnitsMax; }
+size_t score_static_scratch_bytes() { return sizeof(StaticScratch); }
+
+int score_static_item_count(const StaticScorePlan& plan) {
+  int n = 0;
+  for (int i = 0; i < plan.n_units; ++i) n += 4 * (((plan.len_in[i] + plan.n_new + kItemKeys - 1) / kItemKeys + 3) / 4);
+  return n;
+}
+
+// Looks up (once per device, with that device current) where this GPU keeps its copy of `scratch`.
+hipError_t score_static_setup(int device) {
+  if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[device]) return hipSuccess;
+  int cur = -1;
+  hipError_t e = hipGetDevice(&cur);
+  if (e != hipSuccess) return e;
+  if (cur != device && (e = hipSetDevice(device)) != hipSuccess) return e;
+  void* p = nullptr;
+  e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+  if (cur != device) (void)hipSetDevice(cur);
+  if (e != hipSuccess) return e;
+  g_scratch_ptr[device] = static_cast<StaticScratch*>(p);
+  return hipSuccess;
+}
+
+hipError_t launch_score_static(hipStream_t s, int device, int head_dim, const StaticScorePlan& plan, const void* q, int n_obs,
+                               int N_k, float scale, const void* k_cache, const void* k_new, float* importance,
+                               int64_t imp_stride, int* fault) {
+  StaticScratch* sc = (device >= 0 && device < kMaxDevices) ? g_scratch_ptr[device] : nullptr;
+  if (!sc) return hipErrorNotInitialized;
+  const int n_items = score_static_item_count(plan);
+  if (n_items <= 0) return hipSuccess;
+  if (n_items > kStaticItemsMax) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(score_static_plan, dim3(1), dim3(256), 0, s, plan, sc->items, sc->q_rows);
+  // the two-pass form: every slot that pass 2 reads is written by pass 1 of the same call, so the
+  // array needs no clearing between calls
+  launch_score_fused(s, head_dim, kItemKeys, true, sc->items, n_items, q, sc->q_rows, n_obs, N_k, scale, k_cache, k_new,
+                     sc->slots, kMaxGroups, sc->counters, importance, imp_stride, fault, 0,
+                     sc->counters + 2 * kStaticUnitsMax, -1);
+  return hipGetLastError();
 }
 
 void launch_score_generic(hipStream_t s, int head_dim, const UnitDesc* descs, const int32_t* list, int n_list,
