@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--head-variance", action="store_true",
                     help="also time the offline head-classification kernels (attention variance of every unit at the "
                          "final step over the full cache) and report them in a head_variance object")
+    ap.add_argument("--no-full-cache-reference", action="store_true",
+                    help="skip the extra run of the same schedule without compression (full_cache_reference)")
     ap.add_argument("--full-budget", action="store_true",
                     help="reference run: budgets = the whole cache, i.e. the same kernels with no compression "
                          "(plain KV-cache attention over all previous scales)")
@@ -228,18 +230,91 @@ def head_variance_leg(hk, ls, torch, reps=5):
             "sigma_structural_mean": float(sigma.cpu().numpy().reshape(c.batch, c.heads)[:, ls.types == 1].mean())}
 
 
-def committed_traffic(cfg, kernel):
-    """HBM bytes per launch of `kernel` on this workload from the committed
-    counter summary (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, calibrated on
-    a plain copy); None when no summary for this workload is present."""
-    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", f"{kernel}_cfg{cfg.cfg_id}_hbm_traffic.txt")
+def committed_traffic(cfg, kernel, source):
+    """HBM bytes per launch of `kernel` on this workload from the committed counter summary (rocprofv3
+    --pmc FETCH_SIZE / WRITE_SIZE runs, calibrated on a plain copy).  The number is not measured in this
+    run, so its provenance travels with it: the summary records the SHA-256 of the kernel source it was
+    measured on, and `stale` says whether the source has changed since.  None when no summary is present."""
+    import hashlib
+    here = os.path.dirname(os.path.abspath(__file__))
+    path = os.path.join(here, "profiles", f"{kernel}_cfg{cfg.cfg_id}_hbm_traffic.txt")
+    value, measured_sha = None, None
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch"):
-                return float(line.split("=")[1].split()[0])
+                value = float(line.split("=")[1].split()[0])
+            if line.startswith("kernel_source_sha256"):
+                measured_sha = line.split("=")[1].split()[0]
     except OSError:
-        pass
-    return None
+        return None, None
+    try:
+        now_sha = hashlib.sha256(open(os.path.join(here, source), "rb").read()).hexdigest()
+    except OSError:
+        now_sha = None
+    return value, {"file": os.path.relpath(path, here), "kernel_source": source, "measured_on_sha256": measured_sha,
+                   "current_sha256": now_sha, "stale": measured_sha is None or measured_sha != now_sha,
+                   "note": "committed rocprofv3 counter summary, not measured in this run"}
+
+
+def parity_leg(hk, ls, wl, torch, n_units=4):
+    """Device-vs-oracle parity of the timed workload (part of the cpu_baseline leg, outside the timed
+    region): one more eager pass of layer 0 that keeps the kept indices, and the oracle walking the same
+    schedule for a few units of both head classes (oracle.parity.ScheduleChecker)."""
+    from oracle.parity import ScheduleChecker
+    c = ls.cfg
+    types = ls.types
+    ctx = [int(h) for h in np.where(types == 0)[0]]
+    st = [int(h) for h in np.where(types == 1)[0]]
+    units = []
+    for i in range(n_units):
+        pool = ctx if (i % 2 == 0 and ctx) else (st or ctx)
+        b = (i // 2) % c.batch
+        units.append(b * c.heads + pool[(i // 2) % len(pool)])
+    units = sorted(set(units))
+    tol = 1e-4 if c.dtype == "f32" else 2e-2
+    chk = ScheduleChecker(c.heads, c.head_dim, types, c.n_init, c.scale, c.n_obs, units, tol)
+    stride = (c.T_K + 63) // 64 * 64
+    kept = torch.full((c.n_units, stride), -1, dtype=torch.int32, device=ls.q[0].device)
+    ls.mc.reset()
+    L = np.zeros(c.n_units, np.int64)
+    for i in range(c.n_steps):
+        hk.step(ls.mc, ls.q[i], ls.k[i], ls.v[i], types, ls.budgets[i], c.n_init, c.scale, ls.o[i], kept_idx=kept)
+        torch.cuda.synchronize()
+        off, ln = ls.mc.view()
+        t_in = L + c.N[i]
+        L = np.minimum(ls.budgets[i].astype(np.int64), t_in)
+        dev = {}
+        for u in units:
+            b, h = divmod(u, c.heads)
+            dev[u] = dict(I=kept[u, :ln[u]].cpu().numpy() if L[u] < t_in[u] else None,
+                          pos=ls.mc.pos[off[u]:off[u] + ln[u]].cpu().numpy(),
+                          O=ls.o[i][b, h].float().cpu().numpy().astype(np.float64))
+        hst = ls.host[i + 1]
+        chk.step(hst.q, hst.k, hst.v, ls.budgets[i], dev)
+    s = chk.summary()
+    return {"workload": c.name, "layer": ls.layer, "units_checked": len(units), "steps": s["steps"],
+            "kept_sets": {"compared": s["compress_events"], "exact": s["exact"], "excused": s["excused"],
+                          "mismatch": s["mismatch"]},
+            "near_tie_rel": s["near_tie_rel"], "token_id_mismatches": s["pos_mismatch"],
+            "max_abs_dO": s["max_abs_dO"], "tolerance": tol, "ok": not chk.failures}
+
+
+def full_cache_leg(hk, cfg, wl, torch, args, time_schedule, attn_last_us):
+    """The same schedule with budgets that cover the whole cache (no compression: plain KV-cache
+    attention over all previous scales), timed the same way: the reference of the paper's efficiency
+    analysis (whole path and attention at the last scale with and without compression)."""
+    ls = LayerState(hk, cfg, 0, wl, torch, full_budget=True)
+    ls.run(hk)
+    torch.cuda.synchronize()
+    ms = time_schedule([ls], max(4, args.steps // 4), 2)
+    post = ls.mc.as_cache()
+    i = cfg.n_steps - 1
+    last = time_events(torch, lambda: hk.attn(ls.q[i], post, cfg.scale, ls.o[i]), 3)
+    ls.mc.close()
+    return {"budgets": "whole cache", "us_per_layer": ms * 1e3, "attn_last_scale_us": last * 1e3,
+            "keys_per_unit_last_scale": cfg.T_K,
+            "attn_last_scale_us_compressed": attn_last_us,
+            "attn_last_scale_speedup": (last * 1e3) / attn_last_us if attn_last_us else None}
 
 
 def main():
@@ -273,33 +348,38 @@ def main():
     torch.cuda.synchronize()
 
     stream = torch.cuda.Stream()
-    graphs = None
-    if args.mode == "graph":
-        graphs = []
+
+    def time_schedule(lstates, steps, warmup):
+        """ms per layer schedule: `steps` schedules (cycling over lstates) after `warmup` untimed ones."""
+        graphs = None
+        if args.mode == "graph":
+            graphs = []
+            with torch.cuda.stream(stream):
+                for l in lstates:
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=stream):
+                        l.run(hk)
+                    graphs.append(g)
+            torch.cuda.synchronize()
+
+        def one(i):
+            if graphs is not None:
+                graphs[i % len(lstates)].replay()
+            else:
+                lstates[i % len(lstates)].run(hk)
+
         with torch.cuda.stream(stream):
-            for ls in layers:
-                g = torch.cuda.CUDAGraph()
-                with torch.cuda.graph(g, stream=stream):
-                    ls.run(hk)
-                graphs.append(g)
-        torch.cuda.synchronize()
+            for i in range(warmup):
+                one(i)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(steps):
+                one(i)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+        return (t1 - t0) * 1e3 / steps
 
-    def one(i):
-        if graphs is not None:
-            graphs[i % len(layers)].replay()
-        else:
-            layers[i % len(layers)].run(hk)
-
-    with torch.cuda.stream(stream):
-        for i in range(args.warmup):
-            one(i)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(args.steps):
-            one(i)
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = time_schedule(layers, args.steps, args.warmup)
 
     work = wl.work_model(cfg, 0)
     if args.full_budget:   # no compression: every step attends over the whole cache
@@ -344,10 +424,12 @@ def main():
             tf_own = own_flop / (own_ms * 1e-3) / 1e12
             big = [i for i, r in enumerate(work) if r["attn_flop"] > 0.05 * tot["attn_flop"]]
             tf_big = sum(work[i]["attn_flop"] for i in big) / (sum(bd["attn"][i] for i in big) * 1e-3) / 1e12
+            kname = "attn_pipe" if os.environ.get("HACK_ATTN_PIPE", "1") != "0" else "attn_mfma"
+            traffic, traffic_src = committed_traffic(cfg, kname, "paper_2504_09261_amd/csrc/kernels_attn.hip")
             result["roofline"] = {
-                "bound": "mfma", "kernel": "attn_mfma", "achieved": tf_own, "peak": MFMA_BF16_PEAK_TFLOPS,
+                "bound": "mfma", "kernel": kname, "achieved": tf_own, "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": tf_own / MFMA_BF16_PEAK_TFLOPS,
-                "traffic": committed_traffic(cfg, "attn_mfma"),
+                "traffic": traffic, "traffic_source": traffic_src,
                 "steps": [i + 1 for i in own], "launches_per_layer": len(own),
                 "avg_launch_us": own_ms * 1e3 / len(own), "flop_per_launch": own_flop / len(own),
                 "all_attention_launches": {"launches_per_layer": n_attn, "achieved": tf,
@@ -377,8 +459,17 @@ def main():
     if args.head_variance and cfg.dtype == "bf16":
         result["head_variance"] = head_variance_leg(hk, layers[0], torch)
 
+    if not args.no_breakdown and not args.full_budget and not args.no_full_cache_reference:
+        result["full_cache_reference"] = full_cache_leg(hk, cfg, wl, torch, args, time_schedule,
+                                                        result["stages"]["attn"]["per_step_us"][-1])
+        result["full_cache_reference"]["whole_path_speedup"] = result["full_cache_reference"]["us_per_layer"] / result["value"]
+
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(cfg, 0, wl)
+        if not args.full_budget:
+            # the same leg also checks the timed workload against the oracle (outside the timed region)
+            result["parity"] = parity_leg(hk, layers[0], wl, torch)
+            result["cpu_baseline"]["parity"] = result["parity"]
 
     print(json.dumps(result))
 

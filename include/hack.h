@@ -210,6 +210,32 @@ hack_status hack_compact(hack_ctx* ctx, int32_t B, int32_t N_k,
                          const int32_t* kept_idx, int64_t idx_stride,
                          const hack_cache* out, hack_stream stream);
 
+/* ---- final-step merge of contextual heads ---------------------------------
+ * Sec. 4.4, paragraph after the f_C equation ("discarded KV tokens in the last
+ * generation step are softly integrated into their nearest retained counterparts
+ * through similarity-weighted averaging"); supplementary "Compression Setting":
+ * only f_C, only the final generation step.  The paper refers to another work
+ * for the definition; this library's reading: with k_j the key rows of the
+ * uncompressed cache of the step, I the kept rows and E the others,
+ *   n(e) = argmax_{r in I} cos(k_e, k_r)        (ties: lower row index)
+ *   w_e  = max(cos(k_e, k_n(e)), 0)
+ *   K^_r = (k_r + sum_{e in E: n(e) = r} w_e k_e) / (1 + sum w_e),  V^_r likewise
+ * (cosine similarity of key rows; a row of zero norm has similarity 0).
+ * Call it after hack_compact with the same in / k_new / v_new / kept_idx / out:
+ * the rows of `out` are rewritten in place; a kept row nothing was merged into
+ * stays bit for bit as hack_compact wrote it.  Row order and `pos` are unchanged.
+ *   active  HOST [B*H] nonzero = merge this unit (the contextual heads), or NULL = all
+ * Units with out->len[u] == T_in[u] (nothing evicted) are left alone.
+ * Similarities are formed in float32 (bf16 products are exact; dots accumulate in
+ * float32 on the matrix core), the averages in float32 in ascending row order, so
+ * results are reproducible bit for bit.  bf16 contexts only (HACK_EUNSUPPORTED).
+ * Errors: HACK_EINVAL (NULL, a unit that keeps no row or more rows than it has,
+ * output rows overlapping the unit's input rows), HACK_ECAPACITY. */
+hack_status hack_merge(hack_ctx* ctx, int32_t B, int32_t N_k, const hack_cache* in,
+                       const void* k_new, const void* v_new, const int32_t* kept_idx,
+                       int64_t idx_stride, const uint8_t* active, const hack_cache* out,
+                       hack_stream stream);
+
 /* ---- a4: attention of the current scale over the ragged cache -----------
  * Preliminaries, attention equation: O = Softmax(scale * Q K^T) V for every
  * unit over its own kv->len[u] rows, no mask.  out has the layout and element
@@ -288,6 +314,19 @@ hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B,
                       const int32_t* budget, int32_t n_init, float scale,
                       void* out, int32_t* kept_idx_opt, int64_t idx_stride,
                       hack_stream stream);
+
+/* The last scale step of an image: hack_step, and every contextual unit that
+ * compresses at this step merges the rows it discards into the rows it keeps
+ * (hack_merge) before the attention of the step runs over them (Sec. 4.4,
+ * paragraph after the f_C equation; supplementary "Compression Setting").
+ * Structural units and units that do not compress behave as in hack_step.
+ * bf16 contexts only.  Arguments and errors as hack_step. */
+hack_status hack_step_final(hack_ctx* ctx, hack_kvcache* cache, int32_t B,
+                            int32_t N_k, const void* q, const void* k_new,
+                            const void* v_new, const uint8_t* head_type,
+                            const int32_t* budget, int32_t n_init, float scale,
+                            void* out, int32_t* kept_idx_opt, int64_t idx_stride,
+                            hack_stream stream);
 
 #ifdef __cplusplus
 }

@@ -76,8 +76,9 @@ class ScheduleChecker:
                           reseeded=0, max_abs_dO=0.0, pos_mismatch=0, out_of_tol=0)
         self.failures = []
 
-    def step(self, Q, K, V, budgets, device):
+    def step(self, Q, K, V, budgets, device, final_merge=False):
         """Q, K, V: host arrays [B, H, N_k, d] of this scale (the values the device received).
+        final_merge: this is the last generation step (contextual units merge what they discard).
         budgets: int array [B*H].  device: dict unit -> dict with
           'I'   int array, the device's kept indices (only read when the unit compresses),
           'pos' int array, token ids of the rows the device retains after the step (or None),
@@ -92,7 +93,8 @@ class ScheduleChecker:
             Kk = np.asarray(K[b, h], np.float64)
             Vk = np.asarray(V[b, h], np.float64)
             t = int(self.types[h])
-            r = ho.unit_step(Kc, Vc, Pc, Qk, Kk, Vk, self.pos0, t, int(budgets[u]), self.n_init, self.scale, self.n_obs)
+            r = ho.unit_step(Kc, Vc, Pc, Qk, Kk, Vk, self.pos0, t, int(budgets[u]), self.n_init, self.scale, self.n_obs,
+                             final_merge=final_merge)
             dev = device[u]
             if r["compressed"]:
                 self.stats["compress_events"] += 1
@@ -109,7 +111,10 @@ class ScheduleChecker:
                     K_in = np.concatenate([Kc, Kk], axis=0)
                     V_in = np.concatenate([Vc, Vk], axis=0)
                     P_in = np.concatenate([Pc, self.pos0 + np.arange(N_k, dtype=np.int64)])
-                    K2, V2 = ho.compact(K_in, V_in, I_dev)
+                    if final_merge and t == ho.CONTEXTUAL:
+                        K2, V2, _, _ = ho.merge_final(K_in, V_in, I_dev)
+                    else:
+                        K2, V2 = ho.compact(K_in, V_in, I_dev)
                     r = dict(r, K=K2, V=V2, pos=P_in[I_dev], O=ho.attention(Qk, K2, V2, self.scale), I=I_dev)
                     self.stats["reseeded"] += 1
             self.state[u] = (r["K"], r["V"], r["pos"])

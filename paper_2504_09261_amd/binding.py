@@ -23,7 +23,7 @@ EXPORTS = [
     "hack_score", "hack_select", "hack_compact", "hack_attn", "hack_attn_variant",
     "hack_kvcache_rows_required", "hack_kvcache_create", "hack_kvcache_destroy",
     "hack_kvcache_reset", "hack_kvcache_view", "hack_step", "hack_head_variance",
-    "hack_set_score_mode", "hack_get_score_mode", "hack_score_static",
+    "hack_set_score_mode", "hack_get_score_mode", "hack_score_static", "hack_merge", "hack_step_final",
 ]
 
 
@@ -77,6 +77,8 @@ def load_library() -> C.CDLL:
     lib.hack_score_static.argtypes = [vp, i32, i32, vp, pi32, i32, f32, pcache, vp, pu8, vp, i64, vp]
     lib.hack_select.argtypes = [vp, i32, vp, i64, pi32, pu8, pi32, i32, i32, vp, i64, pi32, vp]
     lib.hack_compact.argtypes = [vp, i32, i32, pcache, vp, vp, i32, vp, i64, pcache, vp]
+    lib.hack_merge.argtypes = [vp, i32, i32, pcache, vp, vp, vp, i64, pu8, pcache, vp]
+    lib.hack_step_final.argtypes = [vp, vp, i32, i32, vp, vp, vp, pu8, pi32, i32, f32, vp, vp, i64, vp]
     lib.hack_attn.argtypes = [vp, i32, i32, vp, pcache, f32, vp, vp]
     lib.hack_attn_variant.argtypes = [vp, i32, i32]
     lib.hack_attn_variant.restype = i32
@@ -268,6 +270,13 @@ class Hack:
         self._check(self.lib.hack_compact(self.ctx, B, Nk, C.byref(ci), _dev(k_new), _dev(v_new), pos_new,
                                           _dev(kept_idx), kept_idx.stride(0), C.byref(co), _stream()))
 
+    def merge(self, B: int, Nk: int, cache_in: Cache, kept_idx, cache_out: Cache, k_new=None, v_new=None, active=None):
+        """Final-step merge: evicted rows folded into their nearest kept rows of cache_out (in place)."""
+        ci, co = cache_in.struct(), cache_out.struct()
+        act = None if active is None else _u8(active)
+        self._check(self.lib.hack_merge(self.ctx, B, Nk, C.byref(ci), _dev(k_new), _dev(v_new), _dev(kept_idx),
+                                        kept_idx.stride(0), _p(act, C.c_uint8), C.byref(co), _stream()))
+
     # ---- a4 ----
     def attn(self, q, cache: Cache, scale: float, out):
         B, H, Nk, d = q.shape
@@ -293,9 +302,11 @@ class Hack:
         return ManagedCache(self, cap, with_pos)
 
     def step(self, cache: ManagedCache, q, k_new, v_new, head_type, budget, n_init: int, scale: float, out,
-             kept_idx=None):
+             kept_idx=None, final: bool = False):
+        """final=True: hack_step_final (the last scale step; contextual units merge what they discard)."""
         B, H, Nk, d = q.shape
         ht, bud = _u8(head_type), _i32(budget)
-        self._check(self.lib.hack_step(self.ctx, cache.handle, B, Nk, _dev(q), _dev(k_new), _dev(v_new),
+        fn = self.lib.hack_step_final if final else self.lib.hack_step
+        self._check(fn(self.ctx, cache.handle, B, Nk, _dev(q), _dev(k_new), _dev(v_new),
                                        _p(ht, C.c_uint8), _p(bud, C.c_int32), n_init, scale, _dev(out),
                                        _dev(kept_idx), 0 if kept_idx is None else kept_idx.stride(0), _stream()))

@@ -11,7 +11,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB_NAME = "libhack_mi355x.so"
 LIB_PATH = os.path.join(HERE, LIB_NAME)
 SOURCES = ["hack_api.cpp", "kernels_move.hip", "kernels_select.hip", "kernels_score.hip", "kernels_attn.hip", "kernels_attn_split.hip",
-           "kernels_headvar.hip"]
+           "kernels_headvar.hip", "kernels_merge.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # Packed fp32 VALU forms are switched off for all device code.

@@ -73,6 +73,9 @@ struct hack_ctx {
   int skip_publish = -1;         // test hook: work-group of a fused score launch that withholds its sums
   unsigned* counters = nullptr;  // bf16 path: [max_units, 2] reader counters, zero between launches
   float* hv_stats = nullptr;     // head variance: [max_units, max_queries, 2] softmax statistics of every query
+  int32_t* merge_nn = nullptr;   // final-step merge (bf16): [max_units, ws_stride] nearest kept row of every cache row
+  float* merge_w = nullptr;      //   ... its weight
+  float* merge_inv = nullptr;    //   ... inverse key norms of the kept rows
   int* fault = nullptr;          // pinned, device-visible int[2]: [0] a score wave's bounded wait gave up (fatal),
                                  // [1] a logit exceeded the range the bf16 score kernel supports
   int score_capacity = 0;        // bf16 path: score items one launch may hold (resident waves), default item size
@@ -407,7 +410,7 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (const char* v = std::getenv("HACK_SCORE_TEST_SKIP_PUBLISH")) ctx->skip_publish = std::atoi(v);
   if (const char* v = std::getenv("HACK_SCORE_MODE")) ctx->score_mode = std::atoi(v) == 1 ? HACK_SCORE_TWO_PASS : HACK_SCORE_FUSED;
   if (const char* v = std::getenv("HACK_ATTN_SPLIT_ITEMS")) ctx->split_max_items = std::atoi(v);   // tuning / test override
-  if (const char* v = std::getenv("HACK_ATTN_PIPE")) ctx->attn_kernel = std::max(0, std::min(4, std::atoi(v)));   // A/B and test override
+  if (const char* v = std::getenv("HACK_ATTN_PIPE")) ctx->attn_kernel = std::atoi(v) != 0;   // A/B and test override
   hipError_t e = hipSetDevice(cfg->device);
   const size_t n_ws = (size_t)cfg->max_units * ctx->ws_stride;
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->importance, n_ws * sizeof(float));
@@ -423,6 +426,9 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (e == hipSuccess) ctx->abort_flag = ctx->counters + (size_t)cfg->max_units * 2;
   if (e == hipSuccess && cfg->dtype == HACK_BF16)
     e = hipMalloc((void**)&ctx->hv_stats, (size_t)cfg->max_units * cfg->max_queries * 2 * sizeof(float));
+  if (e == hipSuccess && cfg->dtype == HACK_BF16) e = hipMalloc((void**)&ctx->merge_nn, n_ws * sizeof(int32_t));
+  if (e == hipSuccess && cfg->dtype == HACK_BF16) e = hipMalloc((void**)&ctx->merge_w, n_ws * sizeof(float));
+  if (e == hipSuccess && cfg->dtype == HACK_BF16) e = hipMalloc((void**)&ctx->merge_inv, n_ws * sizeof(float));
   if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->fault, 2 * sizeof(int), hipHostMallocDefault);
   if (e == hipSuccess) ctx->fault[0] = ctx->fault[1] = 0;
   if (e == hipSuccess) e = hipMemset(ctx->rowstat, 0xFF, n_slots * sizeof(unsigned long long));   // every slot empty
@@ -457,6 +463,9 @@ extern "C" void hack_destroy(hack_ctx* ctx) {
   if (ctx->counters) (void)hipFree(ctx->counters);
   if (ctx->fault) (void)hipHostFree(ctx->fault);
   if (ctx->hv_stats) (void)hipFree(ctx->hv_stats);
+  if (ctx->merge_nn) (void)hipFree(ctx->merge_nn);
+  if (ctx->merge_w) (void)hipFree(ctx->merge_w);
+  if (ctx->merge_inv) (void)hipFree(ctx->merge_inv);
   delete ctx->tables;
   delete ctx;
 }
@@ -658,6 +667,60 @@ extern "C" hack_status hack_compact(hack_ctx* ctx, int32_t B, int32_t N_k, const
 }
 
 // ---------------------------------------------------------------------------
+// final-step merge of contextual heads
+// ---------------------------------------------------------------------------
+extern "C" hack_status hack_merge(hack_ctx* ctx, int32_t B, int32_t N_k, const hack_cache* in, const void* k_new,
+                                  const void* v_new, const int32_t* kept_idx, int64_t idx_stride, const uint8_t* active,
+                                  const hack_cache* out, hack_stream stream) {
+  const bool has_new = (k_new != nullptr);
+  hack_status st = check_common(ctx, B, N_k, has_new);
+  if (st != HACK_OK) return st;
+  if (ctx->cfg.dtype != HACK_BF16) return fail(ctx, HACK_EUNSUPPORTED, "the final-step merge is implemented for bf16 contexts");
+  const int U = B * ctx->cfg.heads;
+  if (!kept_idx) return fail(ctx, HACK_EINVAL, "kept_idx is NULL");
+  if (has_new != (v_new != nullptr)) return fail(ctx, HACK_EINVAL, "k_new and v_new must both be given or both be NULL");
+  if (has_new && (!aligned16(k_new) || !aligned16(v_new))) return fail(ctx, HACK_EINVAL, "k_new/v_new must be 16-byte aligned");
+  if ((st = check_cache(ctx, in, U, "in", true)) != HACK_OK) return st;
+  if ((st = check_cache(ctx, out, U, "out", true)) != HACK_OK) return st;
+  const int n_new = has_new ? N_k : 0;
+  std::vector<UnitDesc> descs;
+  std::vector<int32_t> list;
+  int max_t = 0, max_out = 0;
+  for (int u = 0; u < U; ++u) {
+    if (active && !active[u]) continue;
+    const int64_t T = (int64_t)in->len[u] + n_new;
+    const int n = out->len[u];
+    if (n < 1) return fail(ctx, HACK_EINVAL, "unit %d keeps no row", u);
+    if (n > T) return fail(ctx, HACK_EINVAL, "unit %d keeps %d rows of %lld", u, n, (long long)T);
+    if (T > ctx->cfg.max_cache_len) return fail(ctx, HACK_ECAPACITY, "unit %d: T_in = %lld exceeds max_cache_len %d", u, (long long)T, ctx->cfg.max_cache_len);
+    if (n > idx_stride) return fail(ctx, HACK_ECAPACITY, "idx_stride %lld < out->len[%d] = %d", (long long)idx_stride, u, n);
+    if (n == T) continue;   // nothing evicted
+    // the kept rows are rewritten in place while the evicted ones are still read from `in`
+    if ((out->k == in->k || out->v == in->v) && in->len[u] > 0 && out->off[u] < in->off[u] + in->len[u] &&
+        in->off[u] < out->off[u] + n)
+      return fail(ctx, HACK_EINVAL, "output rows of unit %d overlap its input rows", u);
+    UnitDesc d{};
+    d.in_off = in->off[u]; d.out_off = out->off[u]; d.len_in = in->len[u]; d.n_new = n_new; d.n_out = n; d.unit = u;
+    list.push_back((int32_t)descs.size());
+    descs.push_back(d);
+    max_t = std::max(max_t, (int)T);
+    max_out = std::max(max_out, n);
+  }
+  if (descs.empty()) return HACK_OK;
+  Table t;
+  const size_t o_desc = t.add(descs.data(), descs.size());
+  const size_t o_list = t.add(list.data(), list.size());
+  const uint8_t* dev;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
+  launch_merge(s, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), (const int32_t*)(dev + o_list), (int)list.size(), max_t,
+               max_out, in->k, in->v, k_new, v_new, N_k, kept_idx, idx_stride, out->k, out->v, ctx->merge_nn, ctx->merge_w,
+               ctx->merge_inv, ctx->ws_stride);
+  HIP_TRY(ctx, hipGetLastError());
+  return HACK_OK;
+}
+
+// ---------------------------------------------------------------------------
 // a4: attention
 // ---------------------------------------------------------------------------
 extern "C" hack_status hack_attn(hack_ctx* ctx, int32_t B, int32_t N_k, const void* q, const hack_cache* kv,
@@ -794,11 +857,13 @@ extern "C" hack_status hack_kvcache_view(const hack_kvcache* c, hack_cache* view
   return HACK_OK;
 }
 
-extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, int32_t N_k, const void* q,
-                                 const void* k_new, const void* v_new, const uint8_t* head_type,
-                                 const int32_t* budget, int32_t n_init, float scale, void* out,
-                                 int32_t* kept_idx_opt, int64_t idx_stride, hack_stream stream) {
+static hack_status step_impl(hack_ctx* ctx, hack_kvcache* cache, int32_t B, int32_t N_k, const void* q,
+                             const void* k_new, const void* v_new, const uint8_t* head_type,
+                             const int32_t* budget, int32_t n_init, float scale, void* out,
+                             int32_t* kept_idx_opt, int64_t idx_stride, hack_stream stream, bool final_merge) {
   hack_status st = check_common(ctx, B, N_k, true);
+  if (final_merge && ctx->cfg.dtype != HACK_BF16)
+    return fail(ctx, HACK_EUNSUPPORTED, "the final-step merge is implemented for bf16 contexts");
   if (st != HACK_OK) return st;
   const int U = B * ctx->cfg.heads, H = ctx->cfg.heads;
   if (!cache || cache->ctx != ctx || cache->n_units != U) return fail(ctx, HACK_EINVAL, "cache does not belong to this context / batch");
@@ -813,8 +878,8 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
   int32_t* kept = kept_idx_opt ? kept_idx_opt : ctx->kept;
   const int64_t kstride = kept_idx_opt ? idx_stride : ctx->ws_stride;
   std::vector<UnitDesc> descs(U);
-  std::vector<int32_t> comp;
-  int max_t = 0, max_rows = 0;
+  std::vector<int32_t> comp, merging;
+  int max_t = 0, max_rows = 0, merge_t = 0, merge_out = 0;
   for (int u = 0; u < U; ++u) {
     const int L = cache->len[u];
     const int64_t T = (int64_t)L + N_k;
@@ -830,6 +895,11 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
       comp.push_back(u);
       max_t = std::max(max_t, (int)T);
       max_rows = std::max(max_rows, d.n_out);
+      if (final_merge && head_type[u % H] == HACK_CONTEXTUAL) {   // only f_C merges what it discards
+        merging.push_back(u);
+        merge_t = std::max(merge_t, (int)T);
+        merge_out = std::max(merge_out, d.n_out);
+      }
     } else {
       if (T > cache->cap[u]) return fail(ctx, HACK_ECAPACITY, "unit %d: %lld rows do not fit its slab of %d", u, (long long)T, cache->cap[u]);
       d.mode = MOVE_APPEND; d.n_out = (int)T; d.out_off = cache->off[u];
@@ -853,6 +923,7 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
   Table t;
   const size_t o_desc = t.add(descs.data(), descs.size());
   const size_t o_comp = t.add(comp.data(), comp.size());
+  const size_t o_merge = t.add(merging.data(), merging.size());
   const size_t o_rows = t.add(rows, kMaxObs);
   const size_t o_items = t.add(items.data(), items.size());
   const size_t o_sit = t.add(sitems.data(), sitems.size());
@@ -872,6 +943,10 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
   if (!fuse_append)
     launch_move(s, ctx->elem_bytes, ctx->cfg.head_dim, ddev, U, max_rows, cp, cp, k_new, v_new, N_k,
                 (int32_t)cache->tokens_seen, kept, kstride);
+  if (!merging.empty())   // compression, the merge included, precedes the attention of the step
+    launch_merge(s, ctx->cfg.head_dim, ddev, (const int32_t*)(dev + o_merge), (int)merging.size(), merge_t, merge_out,
+                 cache->k, cache->v, k_new, v_new, N_k, kept, kstride, cache->k, cache->v, ctx->merge_nn, ctx->merge_w,
+                 ctx->merge_inv, ctx->ws_stride);
   if (split)
     launch_attn_split(s, ctx->cfg.head_dim, ddev, (const AttnItem*)(dev + o_items), (int)items.size(), q, cache->k,
                       cache->v, k_new, v_new, cache->k, cache->v, cache->pos, (int32_t)cache->tokens_seen,
@@ -890,4 +965,20 @@ extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, 
   }
   cache->tokens_seen += N_k;
   return HACK_OK;
+}
+
+extern "C" hack_status hack_step(hack_ctx* ctx, hack_kvcache* cache, int32_t B, int32_t N_k, const void* q,
+                                 const void* k_new, const void* v_new, const uint8_t* head_type,
+                                 const int32_t* budget, int32_t n_init, float scale, void* out,
+                                 int32_t* kept_idx_opt, int64_t idx_stride, hack_stream stream) {
+  return step_impl(ctx, cache, B, N_k, q, k_new, v_new, head_type, budget, n_init, scale, out, kept_idx_opt, idx_stride,
+                   stream, false);
+}
+
+extern "C" hack_status hack_step_final(hack_ctx* ctx, hack_kvcache* cache, int32_t B, int32_t N_k, const void* q,
+                                       const void* k_new, const void* v_new, const uint8_t* head_type,
+                                       const int32_t* budget, int32_t n_init, float scale, void* out,
+                                       int32_t* kept_idx_opt, int64_t idx_stride, hack_stream stream) {
+  return step_impl(ctx, cache, B, N_k, q, k_new, v_new, head_type, budget, n_init, scale, out, kept_idx_opt, idx_stride,
+                   stream, true);
 }

@@ -145,6 +145,16 @@ void launch_attn_split(hipStream_t s, int head_dim, const UnitDesc* descs, const
 // softmax probabilities.  stats: workspace of 2 floats per (unit, query).
 void launch_head_variance(hipStream_t s, int head_dim, const UnitDesc* descs, int n_desc, int max_len, const void* q,
                           const void* k_cache, int N_k, float scale, float* stats, double* sigma);
+// Final-step merge of the listed units (bf16): every row of the unit's uncompressed cache
+// [rows in_off .. +len_in of k_in / v_in | its N_k rows of k_new / v_new] that kept_idx does not
+// list is folded into its nearest kept row (cosine similarity of keys) by similarity-weighted
+// averaging; the kept rows, which the gather has already written to rows [out_off, out_off + n_out)
+// of k_out / v_out, are updated in place.  list[n_list] indexes descs.  nearest / weight /
+// inv_norm: workspaces of ws_stride entries per unit id (>= the unit's T_in).
+void launch_merge(hipStream_t s, int head_dim, const UnitDesc* descs, const int32_t* list, int n_list, int max_t_in,
+                  int max_out, const void* k_in, const void* v_in, const void* k_new, const void* v_new, int N_k,
+                  const int32_t* kept_idx, int64_t idx_stride, void* k_out, void* v_out, int32_t* nearest, float* weight,
+                  float* inv_norm, int64_t ws_stride);
 // Query rows per attention work item for this dtype/head_dim and launch size.
 int attn_q_tile_rows(int dtype, int head_dim, int n_units, int N_k);
 

@@ -23,19 +23,14 @@
 // enough for the 1e-4 bar and only used for the small fp32 configuration.
 #include <type_traits>
 
+#include "device_util.h"
 #include "hack_internal.h"
 
 namespace hack {
 
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
-typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
-
-constexpr float kLog2eF = 1.4426950408889634f;
+using namespace dev;
 
 // ---------------------------------------------------------------------------
 // fp32 / generic path
@@ -105,57 +100,6 @@ __global__ __launch_bounds__(kGenQ) void attn_generic(
 constexpr int kKB = 32;      // keys per block (one LDS ring slot)
 constexpr float kRescaleAbove = 65536.f;  // a block sum of probabilities at or above this moves the reference
 
-__device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
-  shortx4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (__attribute__((address_space(3))) shortx4*)(p));
-  return __builtin_bit_cast(bf16x4, v);
-}
-
-// K/V tiles go from HBM straight into LDS (global_load_lds, 16 B per lane, one
-// contiguous KiB per wave instruction), so LDS rows cannot be padded; bank
-// conflicts are avoided by a swizzle instead: the 16-byte chunk at position c of
-// LDS row r holds global chunk c ^ f(r).  The LDS moves 256 bytes per clock (64
-// banks of 4 bytes), so one phase of a b128 read covers 16 consecutive lanes (16
-// key rows at one chunk position) and one phase of a transposing b64 read covers
-// 32 lanes (4 key rows x 64 bytes); f spreads those over all 16 chunk slots of
-// 256 bytes:  D=128 (256-byte rows): f_K(r) = r & 15,        f_V(r) = 4 (r & 3)
-//             D=64  (128-byte rows): f_K(r) = (r >> 1) & 7,  f_V(r) = 4 ((r >> 1) & 1)
-// (measured: SQ_LDS_BANK_CONFLICT / SQ_LDS_IDX_ACTIVE was exactly 0.5 with the
-// 32-bank variants r & 7 and 2 (r & 3), and is 0 with these).
-template <int D> __device__ __forceinline__ int swz_k(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
-template <int D> __device__ __forceinline__ int swz_v(int r) { return D == 128 ? 4 * (r & 3) : 4 * ((r >> 1) & 1); }
-
-// The copy is issued from inline assembly so that the compiler does not wait for
-// it before unrelated LDS reads (it would otherwise drain every outstanding LDS
-// write of this kind before the next ds_read, which serialises load and
-// compute).  The matching wait is dma_wait_all(), placed by hand before the
-// barrier that publishes the tile.  base: wave-uniform global address of the
-// tile; voff: this lane's byte offset inside the tile; lds_addr: wave-uniform LDS
-// byte address of the KiB this instruction fills (lane l writes bytes [16l, 16l+16)).
-__device__ __forceinline__ void load_to_lds(const __bf16* base, unsigned voff, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :: "v"(voff), "s"(base), "s"(lds_addr) : "memory", "m0");
-}
-__device__ __forceinline__ void dma_wait_all() {
-  __builtin_amdgcn_sched_barrier(0);  // keep the tile's compute above the wait
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-}
-__device__ __forceinline__ unsigned lds_addr_of(const void* p) {
-  return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
-}
-
-// max over the lane pair (l, l ^ 32) with one VALU swap instead of an LDS permute
-__device__ __forceinline__ float pair_max(float v) {
-  const unsigned u = __builtin_bit_cast(unsigned, v);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return fmaxf(__builtin_bit_cast(float, (unsigned)r[0]), __builtin_bit_cast(float, (unsigned)r[1]));
-}
-__device__ __forceinline__ float pair_sum(float v) {
-  const unsigned u = __builtin_bit_cast(unsigned, v);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
-}
-
 // NW waves per work-group, each wave owns 32 queries; two work-groups share a CU.
 //
 // The loop runs over 32-key blocks and is software-pipelined by one block: while
@@ -179,12 +123,6 @@ __device__ __forceinline__ float pair_sum(float v) {
 //   * the row sum is taken over the bf16-rounded probabilities, the same numbers
 //     the PV product uses.
 constexpr int kRing = 4;     // LDS ring slots per tensor (32-key blocks)
-
-template <int N> __device__ __forceinline__ void dma_wait_but() {
-  __builtin_amdgcn_sched_barrier(0);
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-  __builtin_amdgcn_sched_barrier(0);
-}
 
 template <int D, int NW>
 __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
@@ -491,29 +429,7 @@ __device__ __forceinline__ void sched_interleave() {
   }
 }
 
-// MFMA cluster first (operand reads two ahead), vector work afterwards.
-template <int I, int N, int DS_LEFT>
-__device__ __forceinline__ void sched_cluster() {
-  if constexpr (I < N) {
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-    if constexpr (DS_LEFT >= 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-    else if constexpr (DS_LEFT == 1) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-    sched_cluster<I + 1, N, (DS_LEFT > 2 ? DS_LEFT - 2 : 0)>();
-  }
-}
-
-#ifdef HACK_ATTN_PROF
-__device__ long long g_attn_prof[4096 * 4 * 4];
-#endif
-
-// SCHED: how the three strands of a stage are laid out in the instruction stream
-//   0  every MFMA followed by a slice of the softmax arithmetic and the next operand reads
-//   1  the same, the wave at raised priority from the first to the last MFMA of the stage
-//   2  the 16 MFMAs as one cluster at raised priority, the softmax arithmetic after it at
-//      normal priority (two waves of a SIMD then tend to alternate: one on the matrix core,
-//      the other on the vector ALU)
-//   3  as 2 without the priority changes
-template <int D, int NW, int SCHED>
+template <int D, int NW>
 __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
     const UnitDesc* __restrict__ descs, const AttnItem* __restrict__ items,
     const __bf16* __restrict__ q, const __bf16* __restrict__ k_cache,
@@ -668,10 +584,6 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
   };
 
   bf16x8 pp[2];   // probabilities of the previous block, waiting for their PV product
-#ifdef HACK_ATTN_PROF
-  long long prof_dma = 0, prof_bar = 0, prof_work = 0;
-  const long long prof_start = clock64();
-#endif
 
   // Stage b, ring slot S = b % 3 (compile time).  On entry sc = scores of block b and
   // pp = probabilities of block b-1; on exit sc = scores of block b+1, pp = those of block b.
@@ -683,26 +595,13 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
     constexpr bool FIRST = decltype(first_tag)::value;
     constexpr bool LAST = decltype(last_tag)::value;
     constexpr bool STEADY = decltype(steady_tag)::value;
-#ifdef HACK_ATTN_PROF
-    const long long pt0 = clock64();
-#endif
     // K(b+1) and V(b-1) have landed: everything but the two copy groups issued one stage ago
     if (STEADY) dma_wait_but<2 * IPW>();
     else dma_wait_but<0>();
-#ifdef HACK_ATTN_PROF
-    const long long pt1 = clock64();
-#endif
     __syncthreads();   // both are visible to every wave; the slots of K(b) and V(b-2) are free
-#ifdef HACK_ATTN_PROF
-    const long long pt2 = clock64();
-#endif
     if (STEADY || b + 3 < n_blocks) issue_k(b + 3, S, STEADY);
     if (STEADY || b + 1 < n_blocks) issue_v(b + 1, (S + 1) % NS, STEADY);
     __builtin_amdgcn_sched_barrier(0);
-    if (SCHED == 1 || SCHED == 2) {
-      __builtin_amdgcn_s_setprio(2);
-      __builtin_amdgcn_sched_barrier(0);
-    }
     const __bf16* Kt = &Ks[(S + 1) % NS][0];
     const __bf16* Vt = &Vs[(S + 2) % NS][0];
     floatx16 sn;
@@ -714,14 +613,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
       if (!FIRST) o[i % MB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(v_frag(Vt, i), pp[i / MB], o[i % MB], 0, 0, 0);
     }
     bf16x8 pf[2];
-    float psum;
-    if constexpr (SCHED >= 2) {
-      // all MFMAs of the stage, then the vector work
-      __builtin_amdgcn_sched_barrier(0);
-      if (SCHED == 2) __builtin_amdgcn_s_setprio(0);
-      psum = probs(sc, pf);
-    } else {
-      psum = probs(sc, pf);
+    float psum = probs(sc, pf);
+    {
       // a few operand reads ahead, then per MFMA a slice of the softmax arithmetic and the next reads
       constexpr int N_MFMA = (LAST ? 0 : KK) + (FIRST ? 0 : KK);
       constexpr int N_DS = (LAST ? 0 : KK) + (FIRST ? 0 : 2 * KK);
@@ -731,10 +624,6 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
         __builtin_amdgcn_sched_group_barrier(0x100, AHEAD, 0);
         sched_interleave<0, N_MFMA, VALU_PER, N_DS - AHEAD>();
       }
-      if (SCHED == 1) {
-        __builtin_amdgcn_sched_barrier(0);
-        __builtin_amdgcn_s_setprio(0);
-      }
     }
     if (!STEADY && !LAST) mask_tail(sn, b + 1);
     if (__any(!(psum < kRescaleAbove))) psum = rescale(sc, pf);
@@ -742,13 +631,6 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
     pp[0] = pf[0];
     pp[1] = pf[1];
     if (!LAST) sc = sn;
-#ifdef HACK_ATTN_PROF
-    asm volatile("" ::"v"(o[0]), "v"(o[MB - 1]), "v"(sc));
-    const long long pt3 = clock64();
-    prof_dma += pt1 - pt0;
-    prof_bar += pt2 - pt1;
-    prof_work += pt3 - pt2;
-#endif
   };
 
   using R0 = std::integral_constant<int, 0>;
@@ -815,21 +697,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
       }
     }
   }
-#ifdef HACK_ATTN_PROF
-  if (lane == 0 && blockIdx.x < 4096) {
-    long long* p = g_attn_prof + ((size_t)blockIdx.x * 4 + w) * 4;
-    p[0] = prof_dma; p[1] = prof_bar; p[2] = prof_work; p[3] = clock64() - prof_start;
-  }
-#endif
 }
 
 }  // namespace
 
-#ifdef HACK_ATTN_PROF
-extern "C" int hack_debug_attn_prof(long long* dst, size_t n) {
-  return (int)hipMemcpyFromSymbol(dst, HIP_SYMBOL(g_attn_prof), n * sizeof(long long));
-}
-#endif
 
 // Queries per work item.
 int attn_q_tile_rows(int dtype, int head_dim, int n_units, int N_k) {
@@ -842,14 +713,9 @@ static void launch_mfma_t(hipStream_t s, const UnitDesc* descs, const AttnItem* 
                           const void* q, const void* k_cache, const void* v_cache, int N_k,
                           float scale, void* out, int kernel) {
   typedef __bf16 T;
-#define HACK_PIPE(SCHED_)                                                                                  \
-  hipLaunchKernelGGL((attn_pipe<D, NW, SCHED_>), dim3(n_items), dim3(64 * NW), 0, s, descs, items, \
-                     (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out)
-  if (kernel == 1) HACK_PIPE(0);
-  else if (kernel == 2) HACK_PIPE(1);
-  else if (kernel == 3) HACK_PIPE(2);
-  else if (kernel == 4) HACK_PIPE(3);
-#undef HACK_PIPE
+  if (kernel != 0)
+    hipLaunchKernelGGL((attn_pipe<D, NW>), dim3(n_items), dim3(64 * NW), 0, s, descs, items,
+                       (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out);
   else
     hipLaunchKernelGGL((attn_mfma<D, NW>), dim3(n_items), dim3(64 * NW), 0, s, descs, items,
                        (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out);

@@ -19,67 +19,18 @@
 // concatenation [cached rows | rows of the current scale] and work item t
 // copies rows [32t, 32t+32) of the current scale behind the unit's cached rows,
 // so a step that does not compress needs a single launch.
+#include "device_util.h"
 #include "hack_internal.h"
 
 namespace hack {
 
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
-typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
-typedef __attribute__((__vector_size__(4 * sizeof(short)))) short shortx4;
+using namespace dev;
 
-constexpr float kLog2eF = 1.4426950408889634f;
 constexpr int kKB = 32;        // keys per block
 constexpr int kWaves = 4;      // waves per work-group = key splits
 constexpr int kQTile = 32;     // queries per work item
-
-__device__ __forceinline__ bf16x4 lds_read_tr(const __bf16* p) {
-  shortx4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) shortx4*)(p));
-  return __builtin_bit_cast(bf16x4, v);
-}
-
-// 16-byte chunk c of LDS row r holds global chunk c ^ swz(r): keeps the b128 K reads
-// (16 key rows at one chunk position per phase) and the transposing V reads (4
-// key rows x 64 bytes per phase) free of bank conflicts on the 64-bank LDS.
-template <int D> __device__ __forceinline__ int swz_k(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
-template <int D> __device__ __forceinline__ int swz_v(int r) { return D == 128 ? 4 * (r & 3) : 4 * ((r >> 1) & 1); }
-
-// One KiB per wave instruction, HBM -> LDS without a register round trip: lane l
-// fetches 16 bytes at its own address `src` into LDS bytes [lds_addr + 16 l, +16).
-// Issued from inline assembly so that the compiler does not drain it before
-// unrelated LDS reads; dma_wait_but<N>() is the matching wait.
-__device__ __forceinline__ void load_to_lds(const __bf16* src, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(src), "s"(lds_addr) : "memory", "m0");
-}
-// The same with a wave-uniform base address and a per-lane byte offset (no
-// per-lane 64-bit address arithmetic: the offsets of a full block are loop invariant).
-__device__ __forceinline__ void load_to_lds(const __bf16* base, unsigned voff, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_addr) : "memory", "m0");
-}
-// Waits until at most N of this wave's vector-memory loads are outstanding.
-// Loads return in order, so everything issued before the newest N has landed.
-template <int N> __device__ __forceinline__ void dma_wait_but() {
-  __builtin_amdgcn_sched_barrier(0);
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-  __builtin_amdgcn_sched_barrier(0);
-}
-__device__ __forceinline__ unsigned lds_addr_of(const void* p) {
-  return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
-}
-
-__device__ __forceinline__ float pair_max(float v) {   // over the lane pair (l, l ^ 32)
-  const unsigned u = __builtin_bit_cast(unsigned, v);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return fmaxf(__builtin_bit_cast(float, (unsigned)r[0]), __builtin_bit_cast(float, (unsigned)r[1]));
-}
-__device__ __forceinline__ float pair_sum(float v) {
-  const unsigned u = __builtin_bit_cast(unsigned, v);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
-}
 
 // fuse != 0: keys are [rows in_off .. in_off+len_in of the cache | the unit's n_new
 // rows of k_new / v_new], and those new rows are also written behind the cached

@@ -17,14 +17,14 @@
 // from global memory, one row per lane, runs the memory pipeline at a quarter of
 // its coalesced rate.)  The sums that are subtracted from each other are kept in
 // fp64.
+#include "device_util.h"
 #include "hack_internal.h"
 
 namespace hack {
 
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+using namespace dev;
 
 constexpr int kThreads = 256;          // 4 waves
 constexpr int kWaves = 4;
@@ -33,106 +33,6 @@ constexpr int kRB2 = 2;                // 32-key blocks per wave in pass 2 (64 r
 constexpr int kTile1 = kWaves * 32 * kRB1;  // queries per work-group in pass 1
 constexpr int kTile2 = kWaves * 32 * kRB2;  // keys per work-group in pass 2
 constexpr int kRing = 4;               // LDS ring slots (32-row blocks)
-constexpr float kLog2eF = 1.4426950408889634f;
-
-// 16-byte chunk c of LDS row r holds global chunk c ^ swz(r): b128 operand reads
-// (16 rows at one chunk position per phase) stay free of bank conflicts on the
-// 64-bank LDS, although rows cannot be padded (a copy instruction fills one
-// contiguous KiB).
-template <int D> __device__ __forceinline__ int swz(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
-
-// HBM -> LDS copies, issued from inline assembly so that the compiler does not
-// drain them before unrelated LDS reads; dma_wait_but<N>() is the matching wait
-// (copies complete in order: all but the newest N instructions have landed).
-// base: wave-uniform address; voff: this lane's byte offset; lds_addr:
-// wave-uniform LDS byte address (lane l writes [16 l, +16) resp. [4 l, +4)).
-__device__ __forceinline__ void load_to_lds_x4(const void* base, unsigned voff, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(base), "s"(lds_addr) : "memory", "m0");
-}
-__device__ __forceinline__ void load_to_lds_x1(const void* base, unsigned voff, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(voff), "s"(base), "s"(lds_addr) : "memory", "m0");
-}
-template <int N> __device__ __forceinline__ void dma_wait_but() {
-  __builtin_amdgcn_sched_barrier(0);
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-  __builtin_amdgcn_sched_barrier(0);
-}
-__device__ __forceinline__ unsigned lds_addr_of(const void* p) {
-  return (unsigned)(uintptr_t)(const __attribute__((address_space(3))) void*)p;
-}
-
-// Streams the 32-row blocks of a row-major [n_rows, D] bf16 matrix into an LDS
-// ring of kRing slots; the four waves of the work-group each copy a quarter of
-// a block (IPW instructions).  Rows past the end repeat the last row.
-template <int D>
-struct BlockStream {
-  static constexpr int CPR = D / 8;               // 16-byte chunks per row
-  static constexpr int RPI = 64 / CPR;            // rows per copy instruction
-  static constexpr int IPW = (32 / RPI) / kWaves; // copy instructions per wave and block
-  static constexpr int BLK = 32 * D;              // elements per block
-  const __bf16* base;
-  int n_rows, lane, w;
-  unsigned lds0;
-  unsigned src[IPW];
-  __device__ __forceinline__ void init(const __bf16* base_, int n_rows_, const __bf16* ring, int lane_, int w_) {
-    base = base_; n_rows = n_rows_; lane = lane_; w = w_;
-    lds0 = lds_addr_of(ring);
-#pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-      const int r = (w + i * kWaves) * RPI + lane / CPR, c = lane % CPR;
-      src[i] = (unsigned)(r * D + ((c ^ swz<D>(r)) & (CPR - 1)) * 8) * 2u;
-    }
-  }
-  __device__ __forceinline__ void issue(int b, int slot) const {
-    const int r0 = b * 32;
-    const __bf16* blk = base + (int64_t)r0 * D;
-    if (r0 + 32 <= n_rows) {
-#pragma unroll
-      for (int i = 0; i < IPW; ++i)
-        load_to_lds_x4(blk, src[i], lds0 + (unsigned)((slot * BLK + (w + i * kWaves) * 512) * 2));
-    } else {
-#pragma unroll
-      for (int i = 0; i < IPW; ++i) {
-        const int r = (w + i * kWaves) * RPI + lane / CPR, c = lane % CPR;
-        const int rc = min(r, n_rows - 1 - r0);
-        load_to_lds_x4(blk, (unsigned)(rc * D + ((c ^ swz<D>(r)) & (CPR - 1)) * 8) * 2u,
-                       lds0 + (unsigned)((slot * BLK + (w + i * kWaves) * 512) * 2));
-      }
-    }
-  }
-};
-
-__device__ __forceinline__ float pair_max(float v) {   // over the lane pair (l, l ^ 32)
-  return fmaxf(v, __shfl_xor(v, 32, 64));
-}
-__device__ __forceinline__ float pair_sum(float v) { return v + __shfl_xor(v, 32, 64); }
-
-__device__ __forceinline__ double shfl_xor_f64(double v, int m) {
-  int lo = __double2loint(v), hi = __double2hiint(v);
-  lo = __shfl_xor(lo, m, 64);
-  hi = __shfl_xor(hi, m, 64);
-  return __hiloint2double(hi, lo);
-}
-// sum over the 32 lanes that share a half-wave (lanes differing in bits 0..4)
-__device__ __forceinline__ double half_sum_f64(double v) {
-#pragma unroll
-  for (int m = 1; m < 32; m <<= 1) v += shfl_xor_f64(v, m);
-  return v;
-}
-
-// C register r of lane l after S^T = K Q^T: key row 8(r/4) + 4(l/32) + r%4, query column l%32
-__device__ __forceinline__ int c_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
-
-// Operand fragment of a 32-row block starting at `base` (row-major, D elements per
-// row): lane l takes row min(l%32, n_valid-1) (rows past the end repeat the last
-// valid one), elements [16kk + 8(l/32), +8) at MFMA step kk.
-template <int D>
-__device__ __forceinline__ void load_frags(const __bf16* base, int n_valid, int lane, bf16x8 (&f)[D / 16]) {
-  const int row = min(lane & 31, n_valid - 1);
-  const __bf16* p = base + (int64_t)row * D + 8 * (lane >> 5);
-#pragma unroll
-  for (int kk = 0; kk < D / 16; ++kk) f[kk] = *reinterpret_cast<const bf16x8*>(p + 16 * kk);
-}
 
 template <int D>
 __device__ __forceinline__ floatx16 scores_t(const bf16x8 (&kf)[D / 16], const bf16x8 (&qf)[D / 16]) {
@@ -144,20 +44,13 @@ __device__ __forceinline__ floatx16 scores_t(const bf16x8 (&kf)[D / 16], const b
   return sc;
 }
 
-// Operand fragment kk of the block in an LDS slot: row lane%32, chunk 2kk + lane/32
-template <int D>
-__device__ __forceinline__ bf16x8 lds_frag(const __bf16* slot, int col, int half, int kk) {
-  constexpr int CPR = D / 8;
-  return *reinterpret_cast<const bf16x8*>(&slot[col * D + (((2 * kk + half) ^ swz<D>(col)) & (CPR - 1)) * 8]);
-}
-
 // Pass 1: stats[(u*N_k + i)] = (max_j s_ij, sum_j 2^((s_ij - max) * c2)), s = raw dot product, c2 = scale*log2(e).
 // A wave owns kRB1 blocks of 32 queries (registers); the keys stream through LDS.
 template <int D>
 __global__ __launch_bounds__(kThreads, 2) void hv_rowstats(
     const UnitDesc* __restrict__ descs, const __bf16* __restrict__ q, const __bf16* __restrict__ k_cache,
     int N_k, float scale, float2* __restrict__ stats) {
-  using St = BlockStream<D>;
+  using St = BlockStream<D, kWaves>;
   constexpr int KK = D / 16;
   __shared__ __attribute__((aligned(1024))) __bf16 ring[kRing][St::BLK];
   const UnitDesc d = descs[blockIdx.y];
@@ -234,7 +127,7 @@ template <int D>
 __global__ __launch_bounds__(kThreads, 2) void hv_colmoments(
     const UnitDesc* __restrict__ descs, const __bf16* __restrict__ q, const __bf16* __restrict__ k_cache,
     int N_k, float scale, const float2* __restrict__ stats, double* __restrict__ sigma) {
-  using St = BlockStream<D>;
+  using St = BlockStream<D, kWaves>;
   constexpr int KK = D / 16;
   __shared__ __attribute__((aligned(1024))) __bf16 ring[kRing][St::BLK];
   __shared__ __attribute__((aligned(256))) float2 st_ring[kRing][kWaves][32];
@@ -254,7 +147,7 @@ __global__ __launch_bounds__(kThreads, 2) void hv_colmoments(
   auto issue = [&](int b, int slot) {
     st.issue(b, slot);
     const int qi = min(b * 32 + (lane >> 1), N_k - 1);
-    load_to_lds_x1(stat_base, (unsigned)(qi * 2 + (lane & 1)) * 4u, st_lds + (unsigned)((slot * kWaves + w) * 256));
+    load_to_lds_dword(stat_base, (unsigned)(qi * 2 + (lane & 1)) * 4u, st_lds + (unsigned)((slot * kWaves + w) * 256));
   };
   issue(0, 0);
   if (n_blocks > 1) issue(1, 1);

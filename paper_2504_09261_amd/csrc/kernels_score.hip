@@ -24,14 +24,14 @@
 // the exact value; the ranking that follows is decided on those float32 numbers.
 #include <mutex>
 
+#include "device_util.h"
 #include "hack_internal.h"
 
 namespace hack {
 
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+using namespace dev;
 
 constexpr int kThreads = 256;
 constexpr double kLog2e = 1.4426950408889634074;
@@ -48,13 +48,6 @@ __device__ __forceinline__ double exp_neg(double x) { return (double)exp2_split(
 
 __device__ __forceinline__ float to_float(float v) { return v; }
 __device__ __forceinline__ float to_float(__bf16 v) { return (float)v; }
-
-__device__ __forceinline__ double shfl_xor_f64(double v, int m) {
-  int lo = __double2loint(v), hi = __double2hiint(v);
-  lo = __shfl_xor(lo, m, 64);
-  hi = __shfl_xor(hi, m, 64);
-  return __hiloint2double(hi, lo);
-}
 
 // Combine the per-chunk (reference, sum) partials of one unit into sm[i]
 // (reference) and sinv[i] (1 / normaliser) for the rows i < n_obs.  All 256
@@ -168,11 +161,8 @@ __global__ __launch_bounds__(kThreads) void score_generic(
 // ---------------------------------------------------------------------------
 // bf16 MFMA path
 // ---------------------------------------------------------------------------
-// C = Q~ K^T per 32-key tile: A operand = Q~ (row = observation query l%32),
-// B operand = K^T (column = key l%32); both take the 8 contiguous head-dim
-// elements [16*kk + 8*(l/32), +8) at MFMA step kk.  C register r of lane l is
-// query row 8*(r/4) + 4*(l/32) + r%4, key column l%32.
-__device__ __forceinline__ int c_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
+// C = Q~ K^T per 32-key tile: A operand = Q~ (row = observation query lane%32),
+// B operand = K^T (column = key lane%32); see c_row() for where the results sit.
 
 // ---- wave-private tile pipeline -------------------------------------------
 // A work item is (unit, chunk of 32 TILES keys, TILES = 4 or 8) and belongs to ONE wave: the
@@ -185,25 +175,6 @@ __device__ __forceinline__ int c_row(int r, int half) { return 8 * (r >> 2) + 4 
 // 32 rows x 32 bytes per instruction and re-fetch every cache line several times.
 constexpr int kItemKeys = 128;                 // keys per wave item (TILES = 4), the default
 constexpr int kItemKeysLarge = 256;            // TILES = 8: halves the items when a launch would not hold them all
-
-template <int D> __device__ __forceinline__ int score_swz(int r) { return D == 128 ? (r & 15) : ((r >> 1) & 7); }
-
-__device__ __forceinline__ void score_dma16(const __bf16* src, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-               :: "v"(src), "s"(lds_addr) : "memory", "m0");
-}
-// same copy, source = wave-uniform base (SGPR pair) + per-lane byte offset
-__device__ __forceinline__ void score_dma16_base(const __bf16* base, int voff, unsigned lds_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %0"
-               :: "s"(base), "v"(voff), "s"(lds_addr) : "memory", "m0");
-}
-template <int N> __device__ __forceinline__ void score_wait_vm() {
-  __builtin_amdgcn_sched_barrier(0);
-  if (N == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  else if (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  __builtin_amdgcn_sched_barrier(0);
-}
 
 // Logits are parked in registers between the two halves of the fused kernel as
 // 32-bit fixed point, log2 units with 22 fractional bits: the quantisation moves
@@ -223,25 +194,6 @@ __device__ __forceinline__ double exp2_fix(int qv) {
   const float f = (float)(qv & 0x3FFFFF) * (float)(1.0 / kFixOne);  // [0, 1), exact
   return ldexp((double)__builtin_amdgcn_exp2f(f), n);
 }
-// All-reduce sum over the 32 lanes of a half-wave, fp64, without touching LDS
-// memory: two quad permutes, the two row mirrors (DPP moves of both dwords),
-// then a swizzle across the 16-lane rows.
-template <int CTRL>
-__device__ __forceinline__ double dpp_mov_f64(double v) {
-  const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, true);
-  const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, true);
-  return __hiloint2double(hi, lo);
-}
-__device__ __forceinline__ double half_sum_f64(double v) {
-  v += dpp_mov_f64<0xB1>(v);
-  v += dpp_mov_f64<0x4E>(v);
-  v += dpp_mov_f64<0x141>(v);
-  v += dpp_mov_f64<0x140>(v);
-  const int lo = __builtin_amdgcn_ds_swizzle(__double2loint(v), 0x401F);
-  const int hi = __builtin_amdgcn_ds_swizzle(__double2hiint(v), 0x401F);
-  return v + __hiloint2double(hi, lo);
-}
-
 // One launch, K read once.  Every wave
 //   A. forms the logits t_ij (log2 units) of its item, 32 observation rows x up
 //      to 32 TILES keys, and parks them in registers as fixed point;
@@ -323,7 +275,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
 #pragma unroll
   for (int i = 0; i < IPT; ++i) {
     const int r = i * RPI + lane / CPR, c = lane % CPR;
-    src_off[i] = (r * D + ((c ^ score_swz<D>(r)) & (CPR - 1)) * 8) * 2;
+    src_off[i] = (r * D + ((c ^ swz_k<D>(r)) & (CPR - 1)) * 8) * 2;
   }
   auto issue = [&](int t) {
     const int j0 = key0 + t * 32;
@@ -334,7 +286,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
       const __bf16* base = in_cache ? k_cache + (it.in_off + j0) * D
                                     : k_new + ((int64_t)it.unit * N_k + (j0 - it.len_in)) * D;
 #pragma unroll
-      for (int i = 0; i < IPT; ++i) score_dma16_base(base, src_off[i], dst + i * 1024);
+      for (int i = 0; i < IPT; ++i) load_to_lds(base, (unsigned)src_off[i], dst + i * 1024);
     } else {
 #pragma unroll
       for (int i = 0; i < IPT; ++i) {
@@ -342,7 +294,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
         const int j = min(j0 + r, T_in - 1);
         const __bf16* row = (j < it.len_in) ? k_cache + (it.in_off + j) * D
                                             : k_new + ((int64_t)it.unit * N_k + (j - it.len_in)) * D;
-        score_dma16(row + ((c ^ score_swz<D>(r)) & (CPR - 1)) * 8, dst + i * 1024);
+        load_to_lds(row + ((c ^ swz_k<D>(r)) & (CPR - 1)) * 8, dst + i * 1024);
       }
     }
   };
@@ -372,7 +324,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
 
   int k_off[KK];
 #pragma unroll
-  for (int kk = 0; kk < KK; ++kk) k_off[kk] = col * D + (((2 * kk + half) ^ score_swz<D>(col)) & (CPR - 1)) * 8;
+  for (int kk = 0; kk < KK; ++kk) k_off[kk] = col * D + (((2 * kk + half) ^ swz_k<D>(col)) & (CPR - 1)) * 8;
 
   // ---- A: logits of the item's tiles ---------------------------------------
   int tq[kItemTiles][16];
@@ -381,9 +333,9 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
     if (t < n_tiles) {                 // wave-uniform
       if (t + 1 < n_tiles) {
         issue(t + 1);
-        score_wait_vm<IPT>();          // tile t has landed, tile t+1 stays in flight
+        dma_wait_but<IPT>();          // tile t has landed, tile t+1 stays in flight
       } else {
-        score_wait_vm<0>();
+        dma_wait_but<0>();
       }
       const __bf16* Kt = &tiles[w][t & 1][0];
       // Raw dot products: every MFMA covers 16 head-dim elements and starts from a

@@ -1,0 +1,148 @@
+"""Final-step merge of contextual heads (Sec. 4.4, paragraph after the f_C equation; supplementary
+"Compression Setting") through the C ABI against the CPU oracle: hack_merge on its own, and
+hack_step_final at the end of whole schedules."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hack_oracle as ho
+from paper_2504_09261_amd import workload as wl
+from paper_2504_09261_amd.binding import Cache, HackError
+
+pytestmark = pytest.mark.gpu
+
+BF16_ROUND = 2.0 ** -8        # unit roundoff of bfloat16
+SIM_NEAR_TIE = 2e-5           # float32 dots over d <= 128 exact bf16 products: |error of a cosine| < 1e-5
+
+
+def _u():
+    from tests import gpu_util
+    return gpu_util
+
+
+@pytest.mark.parametrize("d,Nk,lens,keeps", [
+    (128, 300, [1500, 700, 40, 0, 2000, 333], [600, 1000, 5, 300, 31, 633]),
+    (64, 64, [500, 129, 64, 1, 1000, 31], [100, 193, 1, 65, 1064, 33]),
+])
+def test_merge_matches_oracle(d, Nk, lens, keeps):
+    """Ragged units: many and few kept rows, a unit whose cache is only the new rows, one that keeps
+    everything (nothing to merge), an inactive unit; a few planted cases: an evicted copy of a kept
+    row (that row must not change), an evicted all-zero row (weight 0), two identical kept rows (the
+    evicted row that matches both goes to the lower one)."""
+    u = _u()
+    rng = np.random.default_rng(5 + d)
+    H, B, dtype = len(lens), 1, "bf16"
+    hk = u.make_hack(heads=H, head_dim=d, dtype=dtype, max_units=H, max_cache_len=4096, max_queries=512)
+    rows, k_new, v_new = [], u.rand_values(rng, (B, H, Nk, d), dtype), u.rand_values(rng, (B, H, Nk, d), dtype)
+    base = u.rand_values(rng, (24, d), dtype)           # keys cluster around a few directions, as similar tokens do
+    I_all, K_all, V_all = [], [], []
+    for uu, (n, b) in enumerate(zip(lens, keeps)):
+        K = wl.bf16_to_f32(wl.bf16_round(base[rng.integers(0, 24, n)] + 0.5 * u.rand_values(rng, (n, d), dtype)))
+        V = u.rand_values(rng, (n, d), dtype)
+        k_new[0, uu] = wl.bf16_to_f32(wl.bf16_round(base[rng.integers(0, 24, Nk)] + 0.5 * k_new[0, uu]))
+        T = n + Nk
+        b = min(b, T)
+        I = np.sort(rng.choice(T, b, replace=False)).astype(np.int64)
+        Kin, Vin = np.concatenate([K, k_new[0, uu]]), np.concatenate([V, v_new[0, uu]])
+        if uu == 0:
+            ev = np.setdiff1d(np.arange(T), I)
+            Kin[ev[0]], Vin[ev[0]] = Kin[I[3]], Vin[I[3]]      # evicted copy of a kept row
+            Kin[ev[1]] = 0.0                                    # evicted row of zero norm
+            Kin[I[10]] = Kin[I[7]]                              # two identical kept rows ...
+            Kin[ev[2]] = 2.0 * Kin[I[7]]                        # ... and an evicted row parallel to both
+            K, V = Kin[:n], Vin[:n]
+            k_new[0, uu], v_new[0, uu] = Kin[n:], Vin[n:]
+        rows.append((K.astype(np.float32), V.astype(np.float32)))
+        I_all.append(I); K_all.append(Kin.astype(np.float64)); V_all.append(Vin.astype(np.float64))
+    cin, _ = u.build_cache(rows, d, dtype, pad_rows=2, fill=3.0)
+    stride = 4096
+    kept = torch.full((H, stride), -1, dtype=torch.int32, device=u.DEV)
+    for uu in range(H):
+        kept[uu, :len(I_all[uu])] = torch.from_numpy(I_all[uu].astype(np.int32)).to(u.DEV)
+    len_out = np.array([len(I) for I in I_all], np.int32)
+    off_out, total = u.aligned_offsets(len_out, pad_rows=1)
+    cout = Cache(torch.full((total, d), 7.0, dtype=hk.torch_dtype, device=u.DEV),
+                 torch.full((total, d), 7.0, dtype=hk.torch_dtype, device=u.DEV), off_out, len_out)
+    knd, vnd = u.to_dev(k_new, dtype), u.to_dev(v_new, dtype)
+    active = np.ones(H, np.uint8)
+    active[5] = 0
+    hk.compact(B, Nk, cin, kept, cout, knd, vnd)
+    before_k, before_v = cout.k.clone(), cout.v.clone()
+    hk.merge(B, Nk, cin, kept, cout, knd, vnd, active=active)
+    torch.cuda.synchronize()
+    hk.check()
+    Kg_all, Vg_all = u.from_dev(cout.k), u.from_dev(cout.v)
+    # nothing outside the units' rows was written
+    owned = np.zeros(total, bool)
+    for uu in range(H):
+        owned[off_out[uu]:off_out[uu] + len_out[uu]] = True
+    assert np.all(Kg_all[~owned] == 7.0) and np.all(Vg_all[~owned] == 7.0)
+    n_ambiguous = 0
+    for uu in range(H):
+        sl = slice(int(off_out[uu]), int(off_out[uu] + len_out[uu]))
+        Kg, Vg = Kg_all[sl], Vg_all[sl]
+        I, Kin, Vin = I_all[uu], K_all[uu], V_all[uu]
+        if not active[uu] or len(I) == Kin.shape[0]:
+            assert torch.equal(cout.k[sl], before_k[sl]) and torch.equal(cout.v[sl], before_v[sl]), uu
+            continue
+        Kw, Vw, nearest, weight = ho.merge_final(Kin, Vin, I)
+        ev = np.setdiff1d(np.arange(Kin.shape[0]), I)
+        S = ho.key_similarity(Kin[ev], Kin[I])
+        top2 = np.sort(S, axis=1)[:, -2:] if S.shape[1] > 1 else np.concatenate([S - 1, S], axis=1)
+        # evicted rows whose two best kept rows nearly tie (a row that enters with weight 0 changes nothing wherever it goes)
+        amb = ((top2[:, 1] - top2[:, 0]) < SIM_NEAR_TIE) & (top2[:, 1] > SIM_NEAR_TIE)
+        # kept rows such an evicted row may have gone to on either side: not compared
+        skip = np.zeros(len(I), bool)
+        for e_i in np.where(amb)[0]:
+            skip[np.where(S[e_i] >= top2[e_i, 1] - SIM_NEAR_TIE)[0]] = True
+        if uu == 0:
+            skip[[7, 10]] = False                                # the planted exact tie is decided by index on both sides
+        n_ambiguous += int(skip.sum())
+        for G, W in ((Kg, Kw), (Vg, Vw)):
+            ok = np.abs(G - W) <= 1.02 * BF16_ROUND * np.abs(W) + 1e-6
+            assert ok[~skip].all(), (uu, np.where(~ok.all(axis=1) & ~skip)[0][:5])
+        # rows nothing was merged into are bit-exact copies
+        untouched = np.ones(len(I), bool)
+        untouched[nearest[weight > 0]] = False
+        assert np.array_equal(Kg[untouched & ~skip], Kin[I][untouched & ~skip])
+        if uu == 0:
+            assert nearest[list(ev).index(ev[2])] == 7           # lower of the two identical kept rows
+    assert n_ambiguous <= 12, n_ambiguous
+    hk.close()
+
+
+def test_merge_argument_errors_and_fp32():
+    u = _u()
+    hk = u.make_hack(heads=1, head_dim=64, dtype="bf16", max_units=1, max_cache_len=128, max_queries=16)
+    K = torch.zeros((256, 64), dtype=torch.bfloat16, device=u.DEV)
+    kept = torch.zeros((1, 128), dtype=torch.int32, device=u.DEV)
+    cin = Cache(K, K.clone(), [0], [100])
+    with pytest.raises(HackError):                       # keeps more rows than there are
+        hk.merge(1, 16, cin, kept, Cache(K.clone(), K.clone(), [0], [101]))
+    with pytest.raises(HackError):                       # keeps nothing
+        hk.merge(1, 16, cin, kept, Cache(K.clone(), K.clone(), [0], [0]))
+    with pytest.raises(HackError):                       # output rows inside the input rows of the same arrays
+        hk.merge(1, 16, cin, kept, Cache(cin.k, cin.v, [48], [20]))
+    hk.merge(1, 16, cin, kept, Cache(K.clone(), K.clone(), [0], [100]))     # nothing evicted: no work, no error
+    hk.close()
+    hk = u.make_hack(heads=1, head_dim=64, dtype="f32", max_units=1, max_cache_len=128, max_queries=16)
+    Kf = torch.zeros((256, 64), dtype=torch.float32, device=u.DEV)
+    with pytest.raises(HackError) as ei:
+        hk.merge(1, 16, Cache(Kf, Kf.clone(), [0], [100]), kept, Cache(Kf.clone(), Kf.clone(), [0], [50]))
+    assert ei.value.status == -3
+    hk.close()
+
+
+def test_schedules_with_final_merge():
+    """hack_step_final at the last scale of whole schedules: contextual units that compress there hold merged rows
+    and attend over them; structural units and every earlier step are as without the merge."""
+    from tests.test_gpu_schedule import run_free
+    cfg = wl.get_config(1, batch=2)
+    types = wl.head_types(cfg, 0)
+    stats = run_free(cfg, 0, list(range(0, cfg.n_units, 3)), final_merge=True)
+    assert stats["mismatch"] == 0 and stats["merged_rows"] > 0
+    cfg = wl.get_config(2)
+    types = wl.head_types(cfg, 0)
+    units = [int(np.where(types == 0)[0][0]), int(np.where(types == 1)[0][0]), cfg.heads + int(np.where(types == 0)[0][1])]
+    stats = run_free(cfg, 0, units, final_merge=True)
+    assert stats["mismatch"] == 0 and stats["merged_rows"] > 500

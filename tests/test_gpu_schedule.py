@@ -24,8 +24,11 @@ def _tol(cfg):
 PARITY_LOG = []     # one line per whole-schedule run, printed at the end of the session (see conftest)
 
 
+BF16_ROUND = 2.0 ** -8      # unit roundoff of bfloat16: a float32 result stored as bf16 is within this relative distance
+
+
 def run_free(cfg, layer, units, steps=None, types=None, attention=None, with_pos=True, data=None, budgets=None,
-             cap=None, max_excused_frac=0.1):
+             cap=None, max_excused_frac=0.1, final_merge=False):
     """hack_step over the schedule on all units of the workload (free-running, the device keeps its own
     cache); the oracle walks the same schedule for `units` (oracle.parity.ScheduleChecker: kept sets,
     token ids, attention outputs at every step; after an excused near-tie the unit is re-seeded with the
@@ -51,7 +54,8 @@ def run_free(cfg, layer, units, steps=None, types=None, attention=None, with_pos
         q, kn, vn = u.to_dev(st.q, cfg.dtype), u.to_dev(st.k, cfg.dtype), u.to_dev(st.v, cfg.dtype)
         out = torch.empty_like(q)
         kept = torch.full((cfg.n_units, stride), -1, dtype=torch.int32, device=u.DEV)
-        hk.step(mc, q, kn, vn, types, budgets[k - 1], cfg.n_init, cfg.scale, out, kept_idx=kept)
+        last = final_merge and k == n_steps
+        hk.step(mc, q, kn, vn, types, budgets[k - 1], cfg.n_init, cfg.scale, out, kept_idx=kept, final=last)
         torch.cuda.synchronize()
         hk.check()
         off, ln = mc.view()
@@ -64,17 +68,30 @@ def run_free(cfg, layer, units, steps=None, types=None, attention=None, with_pos
             dev[uu] = dict(I=kept[uu, :ln[uu]].cpu().numpy() if L[uu] < t_in[uu] else None,
                            pos=mc.pos[off[uu]:off[uu] + ln[uu]].cpu().numpy() if with_pos else None,
                            O=u.from_dev(out[b, h]))
-        chk.step(st.q, st.k, st.v, budgets[k - 1], dev)
+        chk.step(st.q, st.k, st.v, budgets[k - 1], dev, final_merge=last)
         assert not chk.failures, chk.failures[:5]
     # cache contents are bit-exact copies of the inputs the oracle kept
+    merged_rows = 0
     for uu in units:
         Kw, Vw, _ = chk.final_cache(uu)
         sl = slice(int(off[uu]), int(off[uu] + ln[uu]))
-        assert np.array_equal(u.from_dev(mc.k[sl]), Kw) and np.array_equal(u.from_dev(mc.v[sl]), Vw), uu
+        Kg, Vg = u.from_dev(mc.k[sl]), u.from_dev(mc.v[sl])
+        if final_merge and types[uu % cfg.heads] == 0 and L[uu] < t_in[uu]:
+            # merged rows are float32 averages stored as bf16; an evicted row whose two best similarities nearly
+            # tie may go to the other kept row on the device, which moves two rows: allow a few such rows
+            bad = 0
+            for G, W in ((Kg, Kw), (Vg, Vw)):
+                ok = np.abs(G - W) <= 1.02 * BF16_ROUND * np.abs(W) + 1e-6
+                bad = max(bad, int((~ok.all(axis=1)).sum()))
+            assert bad <= max(2, ln[uu] // 200), (uu, bad, ln[uu])
+            merged_rows += int((np.abs(Kg - Kw).max(axis=1) > 0).sum())
+        else:
+            assert np.array_equal(Kg, Kw) and np.array_equal(Vg, Vw), uu
     mc.close()
     hk.close()
     stats = chk.summary()
     stats["max_err"] = stats["max_abs_dO"]
+    stats["merged_rows"] = merged_rows
     line = (f"parity {cfg.name} layer {layer} ({cfg.n_units} units on the device, {len(units)} through the oracle, "
             f"{n_steps} steps): kept sets exact {stats['exact']} / excused {stats['excused']} / mismatch "
             f"{stats['mismatch']} of {stats['compress_events']}, max |dO| {stats['max_abs_dO']:.3e} (bar {_tol(cfg):g})")
