@@ -78,8 +78,7 @@ struct hack_ctx {
   float* merge_inv = nullptr;    //   ... inverse key norms of the kept rows
   int* fault = nullptr;          // pinned, device-visible int[2]: [0] a score wave's bounded wait gave up (fatal),
                                  // [1] a logit exceeded the range the bf16 score kernel supports
-  int score_capacity = 0;        // bf16 path: score items one launch may hold (resident waves), default item size
-  int score_capacity_large = 0;  // the same for the larger item size
+  int score_capacity[4] = {0, 0, 0, 0};   // bf16 path: score items one fused launch may hold (resident waves) for items of 32, 64, 128, 256 keys
   int split_max_items = 0;       // launches with at most this many 32-query attention items use the key-split kernel
   int attn_kernel = 1;           // bf16 kernel of the 128-query items: 1 = deeper pipeline, 0 = plain (HACK_ATTN_PIPE=0)
   int64_t ws_stride = 0;
@@ -285,6 +284,9 @@ bool use_split_attention(const hack_ctx* ctx, int n_units, int N_k) {
   return (int64_t)n_units * ((N_k + tile - 1) / tile) <= ctx->split_max_items;
 }
 
+int finish_score_plan(const hack_ctx* ctx, const std::vector<UnitDesc>& descs, const std::vector<int32_t>& list, int keys,
+                      std::vector<ScoreItem>* items, std::vector<int>* group_begin);
+
 // One score work item per chunk of every listed unit, longest units first so the
 // tail of a launch is made of short units.  All items of a unit go into the same
 // launch group and no group exceeds `capacity` items; group_begin gets the first
@@ -307,27 +309,54 @@ void build_score_items(const std::vector<UnitDesc>& descs, const std::vector<int
   group_begin->push_back((int)items->size());
 }
 
-// bf16: builds the score items of the listed units.  The default item size is used unless the items would
-// not fit one launch and the larger size gets by with fewer launches (every launch pays the kernel's
-// latency chain again).  Returns the item size chosen.
+// bf16: builds the score items of the listed units and returns the item size (keys per wave) chosen.
+// Smaller items spread a launch over more compute units and shorten every wave's serial tile work, so the
+// smallest size is taken whose items all fit one launch (the fused kernel's work-groups wait for each other
+// inside a launch, so a launch holds at most what the device keeps resident) and whose work-groups per unit the
+// exchange area supports; if no size fits one launch, the size that needs the fewest launches.  The choice
+// does not depend on the score mode, so both modes (and the fixed-scratch entry point, which applies the same
+// rule) group the keys alike and give the same bits.
+int choose_score_item_keys(const hack_ctx* ctx, std::vector<int> t_in) {
+  std::stable_sort(t_in.begin(), t_in.end(), [](int a, int b) { return a > b; });   // the order build_score_items fills launches in
+  int best_keys = 0;
+  long best_launches = 0;
+  for (int i = 0; i < 4; ++i) {
+    const int keys = 32 << i, cap = ctx->score_capacity[i];
+    if (cap <= 0) continue;
+    long launches = 1, in_launch = 0;
+    bool fits = true;
+    for (int t : t_in) {
+      const int wgs = ((t + keys - 1) / keys + 3) / 4;
+      if (wgs > score_max_groups()) { fits = false; break; }
+      if (in_launch + 4 * wgs > cap) { ++launches; in_launch = 0; }
+      in_launch += 4 * wgs;
+    }
+    if (!fits) continue;
+    if (launches <= 1) return keys;
+    if (best_keys == 0 || launches < best_launches) {
+      best_keys = keys;
+      best_launches = launches;
+    }
+  }
+  return best_keys ? best_keys : 256;
+}
+
 int plan_score_items(const hack_ctx* ctx, const std::vector<UnitDesc>& descs, const std::vector<int32_t>& list,
                      std::vector<ScoreItem>* items, std::vector<int>* group_begin) {
-  const int small = score_item_keys(HACK_BF16), large = score_item_keys_large();
-  if (ctx->score_mode == HACK_SCORE_TWO_PASS) {   // no in-kernel wait: one launch pair holds any number of items
-    build_score_items(descs, list, small, INT32_MAX, items, group_begin);
-    return small;
-  }
-  build_score_items(descs, list, small, ctx->score_capacity, items, group_begin);
-  if (group_begin->size() <= 2 || ctx->score_capacity_large <= 0) return small;
-  std::vector<ScoreItem> items_l;
-  std::vector<int> groups_l;
-  build_score_items(descs, list, large, ctx->score_capacity_large, &items_l, &groups_l);
-  if (groups_l.size() < group_begin->size()) {
-    items->swap(items_l);
-    group_begin->swap(groups_l);
-    return large;
-  }
-  return small;
+  std::vector<int> t_in;
+  for (int32_t pos : list) t_in.push_back(descs[pos].len_in + descs[pos].n_new);
+  return finish_score_plan(ctx, descs, list, choose_score_item_keys(ctx, std::move(t_in)), items, group_begin);
+}
+
+// Builds the final item list for the chosen size: launch groups for the fused form, one group for the two-pass
+// form (no in-kernel wait: one launch pair holds any number of items).
+int finish_score_plan(const hack_ctx* ctx, const std::vector<UnitDesc>& descs, const std::vector<int32_t>& list, int keys,
+                      std::vector<ScoreItem>* items, std::vector<int>* group_begin) {
+  int idx = 0;
+  while ((32 << idx) != keys) ++idx;
+  build_score_items(descs, list, keys, ctx->score_mode == HACK_SCORE_TWO_PASS ? INT32_MAX : ctx->score_capacity[idx], items,
+                    group_begin);
+  return keys;
 }
 
 // Scores the listed units of a table that is already on the device.
@@ -416,7 +445,7 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->importance, n_ws * sizeof(float));
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->kept, n_ws * sizeof(int32_t));
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->stats, (size_t)cfg->max_units * ctx->max_chunks * kMaxObs * 2 * sizeof(double));
-  ctx->score_groups = ((cfg->max_cache_len + score_item_keys(HACK_BF16) - 1) / score_item_keys(HACK_BF16) + 3) / 4;
+  ctx->score_groups = score_max_groups();   // exchange slots per unit: enough for every item size
   const size_t n_slots = (size_t)cfg->max_units * ctx->score_groups * kMaxObs;
   ctx->n_slots = n_slots;
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->rowstat, n_slots * sizeof(unsigned long long));
@@ -441,10 +470,10 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (e == hipSuccess && cfg->dtype == HACK_BF16) {
     // a unit's score items wait for each other inside one launch, so a launch may
     // hold at most as many items as the device keeps resident at once
-    ctx->score_capacity = score_fused_capacity(cfg->head_dim, score_item_keys(HACK_BF16));
-    ctx->score_capacity_large = score_fused_capacity(cfg->head_dim, score_item_keys_large());
-    const int per_unit = (cfg->max_cache_len + score_item_keys(cfg->dtype) - 1) / score_item_keys(cfg->dtype) + 3;
-    if (ctx->score_capacity < per_unit || ctx->score_groups > score_max_groups()) e = hipErrorInvalidConfiguration;
+    for (int i = 0; i < 4; ++i) ctx->score_capacity[i] = score_fused_capacity(cfg->head_dim, 32 << i);
+    // the largest unit must fit one launch with the largest items
+    const int per_unit = (cfg->max_cache_len + 255) / 256 + 3;
+    if (ctx->score_capacity[3] < per_unit || (per_unit + 3) / 4 > score_max_groups()) e = hipErrorInvalidConfiguration;
   }
   if (e != hipSuccess) {
     hack_destroy(ctx);
@@ -561,6 +590,11 @@ extern "C" hack_status hack_score_static(hack_ctx* ctx, int32_t B, int32_t N_k, 
     ++plan.n_units;
   }
   if (plan.n_units == 0) return HACK_OK;
+  {   // the item size hack_score would take for these units: same grouping of the keys, same bits
+    std::vector<int> t_in;
+    for (int i = 0; i < plan.n_units; ++i) t_in.push_back(plan.len_in[i] + plan.n_new);
+    plan.item_keys = choose_score_item_keys(ctx, std::move(t_in));
+  }
   fill_q_rows(q_idx, n_obs, N_k, plan.q_rows);
   HIP_TRY(ctx, launch_score_static(static_cast<hipStream_t>(stream), ctx->cfg.device, ctx->cfg.head_dim, plan, q, n_obs, N_k, scale,
                                    in->k, k_new, importance, imp_stride, ctx->fault));

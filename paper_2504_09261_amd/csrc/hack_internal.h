@@ -54,7 +54,7 @@ void launch_move(hipStream_t s, int elem_bytes, int head_dim, const UnitDesc* de
                  int N_k, int pos_new, const int32_t* kept_idx, int64_t idx_stride);
 
 // Subset-attention importance, bf16: one launch over `items`, a DEVICE array with
-// one entry per chunk of item_keys keys (score_item_keys() or score_item_keys_large()) of every scored unit, each unit
+// one entry per chunk of item_keys keys (32, 64, 128 or 256) of every scored unit, each unit
 // padded with empty chunks to a multiple of 4 entries (one work-group takes 4
 // consecutive entries, which must belong to one unit).  All items of a unit
 // must be in the same launch and n_items must not exceed
@@ -77,7 +77,6 @@ struct alignas(16) ScoreItem {
 static_assert(sizeof(ScoreItem) == 32, "ScoreItem must stay 32 bytes");
 int score_item_keys(int dtype);
 int score_max_groups();   // work-groups per unit the fused kernel's exchange supports
-int score_item_keys_large();   // bf16: the larger item size, used when the default would not fit one launch
 int score_fused_capacity(int head_dim, int item_keys);
 // two_pass: two launches (row sums, then importance) that read K twice but never wait inside
 // a launch, so n_items may then exceed the resident capacity and other kernels may share the
@@ -100,6 +99,7 @@ struct StaticScorePlan {
   int32_t q_rows[kMaxObs];
   int32_t n_units;
   int32_t n_new;                     // rows of k_new that follow the cached ones (0 or N_k)
+  int32_t item_keys;                 // keys per wave item: 32, 64, 128 or 256
 };
 int score_static_units_max();
 size_t score_static_scratch_bytes();

@@ -165,7 +165,7 @@ __global__ __launch_bounds__(kThreads) void score_generic(
 // B operand = K^T (column = key lane%32); see c_row() for where the results sit.
 
 // ---- wave-private tile pipeline -------------------------------------------
-// A work item is (unit, chunk of 32 TILES keys, TILES = 4 or 8) and belongs to ONE wave: the
+// A work item is (unit, chunk of 32 TILES keys, TILES = 1, 2, 4 or 8) and belongs to ONE wave: the
 // wave copies its 32-key tiles HBM -> LDS with global_load_lds (16 B per lane,
 // whole rows, fully coalesced), double-buffered in a private LDS region, and
 // reads MFMA operands back with ds_read_b128 (XOR-swizzled chunks, conflict
@@ -173,8 +173,7 @@ __global__ __launch_bounds__(kThreads) void score_generic(
 // wait on their own copies (hand-placed s_waitcnt vmcnt), so they drift freely and
 // keep HBM busy.  Reading K fragments straight from HBM in operand layout would touch
 // 32 rows x 32 bytes per instruction and re-fetch every cache line several times.
-constexpr int kItemKeys = 128;                 // keys per wave item (TILES = 4), the default
-constexpr int kItemKeysLarge = 256;            // TILES = 8: halves the items when a launch would not hold them all
+constexpr int kItemKeys = 128;                 // keys per wave item that the workspace sizes of the fp32 path refer to
 
 // Logits are parked in registers between the two halves of the fused kernel as
 // 32-bit fixed point, log2 units with 22 fractional bits: the quantisation moves
@@ -327,7 +326,15 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
   for (int kk = 0; kk < KK; ++kk) k_off[kk] = col * D + (((2 * kk + half) ^ swz_k<D>(col)) & (CPR - 1)) * 8;
 
   // ---- A: logits of the item's tiles ---------------------------------------
-  int tq[kItemTiles][16];
+  // Between A and C a logit waits in registers either as its fixed-point value (one register; 2^t is
+  // formed again in C) or, for the small items (TILES <= 2, where the registers are there), as the
+  // double 2^t of that same fixed-point value (two registers; nothing is recomputed).  Both forms give
+  // the same numbers bit for bit.
+  constexpr bool kParkP = TILES <= 2;
+  int tq[kParkP ? 1 : kItemTiles][16];
+  double pq[kParkP ? kItemTiles : 1][16];
+  auto p_of = [&](int t, int r) -> double { return kParkP ? pq[t][r] : exp2_fix(tq[t][r]); };
+  int q_hi = 0, q_lo = 0;              // extremes of the fixed-point logits, for the clamp report
 #pragma unroll
   for (int t = 0; t < kItemTiles; ++t) {
     if (t < n_tiles) {                 // wave-uniform
@@ -353,27 +360,26 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
         for (int r = 0; r < 16; ++r) sd[r] += (double)c[r];
       }
 #pragma unroll
-      for (int r = 0; r < 16; ++r) tq[t][r] = fix_from(sd[r] * c2);
+      for (int r = 0; r < 16; ++r) {
+        const int qv = fix_from(sd[r] * c2);
+        q_hi = max(q_hi, qv);
+        q_lo = min(q_lo, qv);
+        if (kParkP) pq[t][r] = exp2_fix(qv);
+        else tq[t][r] = qv;
+      }
     } else {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) tq[t][r] = 0;
+      for (int r = 0; r < 16; ++r) {
+        if (kParkP) pq[t][r] = 0.0;
+        else tq[t][r] = 0;
+      }
     }
   }
 
   // A logit that hit the clamp of the parked format makes the result differ from
   // the definition: tell the host (second flag word; the launch still completes).
-  {
-    int hi = tq[0][0], lo = tq[0][0];
-#pragma unroll
-    for (int t = 0; t < kItemTiles; ++t)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        hi = max(hi, tq[t][r]);
-        lo = min(lo, tq[t][r]);
-      }
-    if (__any(hi >= kFixLimit || lo <= -kFixLimit)) {
-      if (lane == 0) __hip_atomic_store(fault + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    }
+  if (__any(q_hi >= kFixLimit || q_lo <= -kFixLimit)) {
+    if (lane == 0) __hip_atomic_store(fault + 1, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
   }
 
   // ---- B: row sums of the work-group -> its slot ------------------------------
@@ -387,7 +393,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
     double lsum = 0.0;
 #pragma unroll
     for (int t = 0; t < kItemTiles; ++t)
-      if (t < n_tiles && key0 + t * 32 + col < T_in) lsum += exp2_fix(tq[t][r]);
+      if (t < n_tiles && key0 + t * 32 + col < T_in) lsum += p_of(t, r);
     const double l = half_sum_f64(lsum);
     if (col == 0) red[c_row(r, half)] = l;
   }
@@ -469,7 +475,7 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
     if (t < n_tiles) {
       double imp = 0.0;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) imp = fma(exp2_fix(tq[t][r]), inv_r[r], imp);
+      for (int r = 0; r < 16; ++r) imp = fma(p_of(t, r), inv_r[r], imp);
       imp += shfl_xor_f64(imp, 32);
       const int j = key0 + t * 32 + col;
       if (j < T_in && half == 0) importance[(int64_t)it.unit * imp_stride + j] = (float)imp;
@@ -502,20 +508,23 @@ void launch_generic(hipStream_t s, dim3 grid, const UnitDesc* descs, const int32
 }  // namespace
 
 int score_item_keys(int dtype) { return dtype == 1 ? kScoreChunk : kItemKeys; }
-int score_item_keys_large() { return kItemKeysLarge; }
 int score_max_groups() { return kMaxGroups; }
 
+// Items (= waves) of one fused launch the device keeps resident at once, for items of item_keys keys.
 int score_fused_capacity(int head_dim, int item_keys) {
   int dev = 0, cus = 0, blocks = 0;
   if (hipGetDevice(&dev) != hipSuccess) return 0;
   if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-  hipError_t e;
-  if (item_keys == kItemKeysLarge)
-    e = head_dim == 64 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<64, 8, kScoreFused>, kThreads, 0)
-                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<128, 8, kScoreFused>, kThreads, 0);
-  else
-    e = head_dim == 64 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<64, 4, kScoreFused>, kThreads, 0)
-                       : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<128, 4, kScoreFused>, kThreads, 0);
+  hipError_t e = hipErrorInvalidValue;
+#define HACK_OCC(D_, TILES_) hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, score_fused<D_, TILES_, kScoreFused>, kThreads, 0)
+  switch (item_keys) {
+    case 32: e = head_dim == 64 ? HACK_OCC(64, 1) : HACK_OCC(128, 1); break;
+    case 64: e = head_dim == 64 ? HACK_OCC(64, 2) : HACK_OCC(128, 2); break;
+    case 128: e = head_dim == 64 ? HACK_OCC(64, 4) : HACK_OCC(128, 4); break;
+    case 256: e = head_dim == 64 ? HACK_OCC(64, 8) : HACK_OCC(128, 8); break;
+    default: break;
+  }
+#undef HACK_OCC
   if (e != hipSuccess) return 0;
   return blocks * cus * (kThreads / 64);
 }
@@ -549,13 +558,20 @@ void launch_score_fused(hipStream_t s, int head_dim, int item_keys, bool two_pas
   launch_score_t<D_, TILES_>(s, grid, two_pass, items, n_items, (const T*)q, q_rows, n_obs, N_k, scale, (const T*)k_cache, \
                              (const T*)k_new, slots, slot_groups, counters, importance, imp_stride, fault, spin_limit,  \
                              abort_flag, skip_publish)
-  const bool large = item_keys == kItemKeysLarge;
   if (head_dim == 64) {
-    if (large) HACK_SCORE_CALL(64, 8);
-    else HACK_SCORE_CALL(64, 4);
+    switch (item_keys) {
+      case 32: HACK_SCORE_CALL(64, 1); break;
+      case 64: HACK_SCORE_CALL(64, 2); break;
+      case 256: HACK_SCORE_CALL(64, 8); break;
+      default: HACK_SCORE_CALL(64, 4); break;
+    }
   } else {
-    if (large) HACK_SCORE_CALL(128, 8);
-    else HACK_SCORE_CALL(128, 4);
+    switch (item_keys) {
+      case 32: HACK_SCORE_CALL(128, 1); break;
+      case 64: HACK_SCORE_CALL(128, 2); break;
+      case 256: HACK_SCORE_CALL(128, 8); break;
+      default: HACK_SCORE_CALL(128, 4); break;
+    }
   }
 #undef HACK_SCORE_CALL
 }
@@ -593,7 +609,7 @@ __global__ __launch_bounds__(256) void score_static_plan(StaticScorePlan plan, S
     for (int i = 0; i < plan.n_units; ++i) {
       first[i] = n;
       const int t_in = plan.len_in[i] + plan.n_new;
-      n += 4 * (((t_in + kItemKeys - 1) / kItemKeys + 3) / 4);
+      n += 4 * (((t_in + plan.item_keys - 1) / plan.item_keys + 3) / 4);
     }
     first[plan.n_units] = n;
   }
@@ -614,7 +630,8 @@ size_t score_static_scratch_bytes() { return sizeof(StaticScratch); }
 
 int score_static_item_count(const StaticScorePlan& plan) {
   int n = 0;
-  for (int i = 0; i < plan.n_units; ++i) n += 4 * (((plan.len_in[i] + plan.n_new + kItemKeys - 1) / kItemKeys + 3) / 4);
+  for (int i = 0; i < plan.n_units; ++i)
+    n += 4 * (((plan.len_in[i] + plan.n_new + plan.item_keys - 1) / plan.item_keys + 3) / 4);
   return n;
 }
 
@@ -646,7 +663,7 @@ hipError_t launch_score_static(hipStream_t s, int device, int head_dim, const St
   hipLaunchKernelGGL(score_static_plan, dim3(1), dim3(256), 0, s, plan, sc->items, sc->q_rows);
   // the two-pass form: every slot that pass 2 reads is written by pass 1 of the same call, so the
   // array needs no clearing between calls
-  launch_score_fused(s, head_dim, kItemKeys, true, sc->items, n_items, q, sc->q_rows, n_obs, N_k, scale, k_cache, k_new,
+  launch_score_fused(s, head_dim, plan.item_keys, true, sc->items, n_items, q, sc->q_rows, n_obs, N_k, scale, k_cache, k_new,
                      sc->slots, kMaxGroups, sc->counters, importance, imp_stride, fault, 0,
                      sc->counters + 2 * kStaticUnitsMax, -1);
   return hipGetLastError();

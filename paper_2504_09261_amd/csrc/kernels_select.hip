@@ -8,6 +8,8 @@
 // value tau and how many rows equal to tau are still needed; an index-ordered
 // prefix scan then emits kept rows in ascending order, taking the tau-equal
 // rows with the lowest indices first (lowest-index tie-break for free).
+#include <mutex>
+
 #include "hack_internal.h"
 
 namespace hack {
@@ -80,9 +82,27 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     for (int shift = 24; shift >= 0; shift -= 8) {
       if (tid < 256) hist[tid] = 0;
       __syncthreads();
-      for (int i = tid; i < n_sel; i += kThreads) {
-        const uint32_t k = keys[i];
-        if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+      if (shift == 24) {
+        // Importance values of one unit mostly share sign and exponent, so in the first pass nearly all
+        // keys fall into a handful of bins and per-lane LDS atomics would serialise on them: a wave
+        // counts its lanes per distinct bin first (a few rounds) and adds once per bin.
+        for (int i0 = 0; i0 < n_sel; i0 += kThreads) {
+          const int i = i0 + tid;
+          const bool valid = i < n_sel;
+          const uint32_t bin = valid ? (keys[i] >> 24) : 0u;
+          unsigned long long todo = __ballot(valid);
+          while (todo) {
+            const uint32_t b0 = __shfl(bin, __builtin_ctzll(todo), 64);
+            const unsigned long long same = __ballot(valid && bin == b0);
+            if ((tid & 63) == __builtin_ctzll(same)) atomicAdd(&hist[b0], (uint32_t)__builtin_popcountll(same));
+            todo &= ~same;
+          }
+        }
+      } else {
+        for (int i = tid; i < n_sel; i += kThreads) {
+          const uint32_t k = keys[i];
+          if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+        }
       }
       __syncthreads();
       if (tid < 64) {
@@ -161,11 +181,20 @@ void launch_select(hipStream_t s, const UnitDesc* descs, const int32_t* list, in
                    int64_t idx_stride) {
   if (n_list <= 0) return;
   const size_t lds = select_lds_bytes(max_t_in);
-  static size_t configured = 0;
-  if (lds > 48 * 1024 && lds > configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    configured = lds;
+  if (lds > 48 * 1024) {
+    // larger dynamic LDS has to be allowed once per device: raise the limit to the largest unit the library
+    // supports the first time a device needs it
+    static std::mutex mu;
+    static bool configured[64] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64) {
+      std::lock_guard<std::mutex> lock(mu);
+      if (!configured[dev]) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)select_lds_bytes(32768));
+        configured[dev] = true;
+      }
+    }
   }
   hipLaunchKernelGGL(select_kernel, dim3(n_list), dim3(kThreads), lds, s, descs, list, importance,
                      imp_stride, kept_idx, idx_stride);
