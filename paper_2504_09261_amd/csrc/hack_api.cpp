@@ -65,6 +65,7 @@ struct hack_ctx {
   int32_t* kept = nullptr;       // [max_units, ws_stride]
   double* stats = nullptr;       // fp32 path: [max_units, max_chunks, 32, 2] softmax partials
   unsigned long long* rowstat = nullptr;  // bf16 path: [max_units, score_groups, 32] row-sum exchange slots, all-ones between launches
+  unsigned long long* rowstat_side = nullptr;  // the same for the side branch of hack_step (two-pass form: its slots are not re-armed)
   int score_groups = 0;          // work-groups a unit of max_cache_len keys is scored by
   int spin_limit = 0;            // polls after which a score work-group gives up its wait for the unit's other work-groups
   unsigned* abort_flag = nullptr; // bf16 path: device word behind the counters; set by a fused score launch that gave up
@@ -81,6 +82,10 @@ struct hack_ctx {
   int score_capacity[4] = {0, 0, 0, 0};   // bf16 path: score items one fused launch may hold (resident waves) for items of 32, 64, 128, 256 keys
   int split_max_items = 0;       // launches with at most this many 32-query attention items use the key-split kernel
   int attn_kernel = 1;           // bf16 kernel of the 128-query items: 1 = deeper pipeline, 0 = plain (HACK_ATTN_PIPE=0)
+  // hack_step overlap: the compression chain of one group of units runs beside the attention of the other group
+  bool step_overlap = false;     // off by default (measured slower on MI355X, see step_impl); HACK_STEP_OVERLAP=1 switches it on
+  hipStream_t aux_stream = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   int64_t ws_stride = 0;
   int max_chunks = 0;
   // launch-table cache: tables keep their device address for the life of the context
@@ -285,7 +290,7 @@ bool use_split_attention(const hack_ctx* ctx, int n_units, int N_k) {
 }
 
 int finish_score_plan(const hack_ctx* ctx, const std::vector<UnitDesc>& descs, const std::vector<int32_t>& list, int keys,
-                      std::vector<ScoreItem>* items, std::vector<int>* group_begin);
+                      bool two_pass, std::vector<ScoreItem>* items, std::vector<int>* group_begin);
 
 // One score work item per chunk of every listed unit, longest units first so the
 // tail of a launch is made of short units.  All items of a unit go into the same
@@ -341,26 +346,25 @@ int choose_score_item_keys(const hack_ctx* ctx, std::vector<int> t_in) {
   return best_keys ? best_keys : 256;
 }
 
-int plan_score_items(const hack_ctx* ctx, const std::vector<UnitDesc>& descs, const std::vector<int32_t>& list,
+int plan_score_items(const hack_ctx* ctx, const std::vector<UnitDesc>& descs, const std::vector<int32_t>& list, bool two_pass,
                      std::vector<ScoreItem>* items, std::vector<int>* group_begin) {
   std::vector<int> t_in;
   for (int32_t pos : list) t_in.push_back(descs[pos].len_in + descs[pos].n_new);
-  return finish_score_plan(ctx, descs, list, choose_score_item_keys(ctx, std::move(t_in)), items, group_begin);
+  return finish_score_plan(ctx, descs, list, choose_score_item_keys(ctx, std::move(t_in)), two_pass, items, group_begin);
 }
 
 // Builds the final item list for the chosen size: launch groups for the fused form, one group for the two-pass
 // form (no in-kernel wait: one launch pair holds any number of items).
 int finish_score_plan(const hack_ctx* ctx, const std::vector<UnitDesc>& descs, const std::vector<int32_t>& list, int keys,
-                      std::vector<ScoreItem>* items, std::vector<int>* group_begin) {
+                      bool two_pass, std::vector<ScoreItem>* items, std::vector<int>* group_begin) {
   int idx = 0;
   while ((32 << idx) != keys) ++idx;
-  build_score_items(descs, list, keys, ctx->score_mode == HACK_SCORE_TWO_PASS ? INT32_MAX : ctx->score_capacity[idx], items,
-                    group_begin);
+  build_score_items(descs, list, keys, two_pass ? INT32_MAX : ctx->score_capacity[idx], items, group_begin);
   return keys;
 }
 
 // Scores the listed units of a table that is already on the device.
-void run_score(hack_ctx* ctx, hipStream_t s, const UnitDesc* ddev, const int32_t* list_dev, int n_list, int max_t,
+void run_score(hack_ctx* ctx, hipStream_t s, bool two_pass, unsigned long long* slots, const UnitDesc* ddev, const int32_t* list_dev, int n_list, int max_t,
                const ScoreItem* items_dev, int item_keys, const std::vector<int>& group_begin, const void* q,
                const int32_t* rows_dev, int n_obs, int N_k, float scale, const void* k_cache, const void* k_new,
                float* importance, int64_t imp_stride) {
@@ -370,8 +374,8 @@ void run_score(hack_ctx* ctx, hipStream_t s, const UnitDesc* ddev, const int32_t
     return;
   }
   for (size_t g = 0; g + 1 < group_begin.size(); ++g)
-    launch_score_fused(s, ctx->cfg.head_dim, item_keys, ctx->score_mode == HACK_SCORE_TWO_PASS, items_dev + group_begin[g],
-                       group_begin[g + 1] - group_begin[g], q, rows_dev, n_obs, N_k, scale, k_cache, k_new, ctx->rowstat,
+    launch_score_fused(s, ctx->cfg.head_dim, item_keys, two_pass, items_dev + group_begin[g],
+                       group_begin[g + 1] - group_begin[g], q, rows_dev, n_obs, N_k, scale, k_cache, k_new, slots,
                        ctx->score_groups, ctx->counters, importance, imp_stride, ctx->fault, ctx->spin_limit, ctx->abort_flag,
                        ctx->skip_publish);
 }
@@ -439,6 +443,7 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (const char* v = std::getenv("HACK_SCORE_TEST_SKIP_PUBLISH")) ctx->skip_publish = std::atoi(v);
   if (const char* v = std::getenv("HACK_SCORE_MODE")) ctx->score_mode = std::atoi(v) == 1 ? HACK_SCORE_TWO_PASS : HACK_SCORE_FUSED;
   if (const char* v = std::getenv("HACK_ATTN_SPLIT_ITEMS")) ctx->split_max_items = std::atoi(v);   // tuning / test override
+  if (const char* v = std::getenv("HACK_STEP_OVERLAP")) ctx->step_overlap = std::atoi(v) != 0;
   if (const char* v = std::getenv("HACK_ATTN_PIPE")) ctx->attn_kernel = std::atoi(v) != 0;   // A/B and test override
   hipError_t e = hipSetDevice(cfg->device);
   const size_t n_ws = (size_t)cfg->max_units * ctx->ws_stride;
@@ -449,6 +454,7 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   const size_t n_slots = (size_t)cfg->max_units * ctx->score_groups * kMaxObs;
   ctx->n_slots = n_slots;
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->rowstat, n_slots * sizeof(unsigned long long));
+  if (e == hipSuccess && cfg->dtype == HACK_BF16) e = hipMalloc((void**)&ctx->rowstat_side, n_slots * sizeof(unsigned long long));
   const size_t n_counters = (size_t)cfg->max_units * 2 + 64;   // per-unit reader counters, then the abort word
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->counters, n_counters * sizeof(unsigned));
   if (e == hipSuccess) e = hipMemset(ctx->counters, 0, n_counters * sizeof(unsigned));
@@ -466,6 +472,9 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
     ctx->tables = new (std::nothrow) TableCache<HipTableBackend>(HipTableBackend{}, kTableChunkBytes, kTableLimitBytes);
     if (!ctx->tables || !ctx->tables->reserve_first_chunk()) e = hipErrorOutOfMemory;
   }
+  if (e == hipSuccess) e = hipStreamCreateWithFlags(&ctx->aux_stream, hipStreamNonBlocking);   // default priority
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming);
+  if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming);
   if (e == hipSuccess) e = score_static_setup(cfg->device);   // device address of the library's fixed scratch array
   if (e == hipSuccess && cfg->dtype == HACK_BF16) {
     // a unit's score items wait for each other inside one launch, so a launch may
@@ -489,12 +498,16 @@ extern "C" void hack_destroy(hack_ctx* ctx) {
   if (ctx->kept) (void)hipFree(ctx->kept);
   if (ctx->stats) (void)hipFree(ctx->stats);
   if (ctx->rowstat) (void)hipFree(ctx->rowstat);
+  if (ctx->rowstat_side) (void)hipFree(ctx->rowstat_side);
   if (ctx->counters) (void)hipFree(ctx->counters);
   if (ctx->fault) (void)hipHostFree(ctx->fault);
   if (ctx->hv_stats) (void)hipFree(ctx->hv_stats);
   if (ctx->merge_nn) (void)hipFree(ctx->merge_nn);
   if (ctx->merge_w) (void)hipFree(ctx->merge_w);
   if (ctx->merge_inv) (void)hipFree(ctx->merge_inv);
+  if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+  if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
+  if (ctx->aux_stream) (void)hipStreamDestroy(ctx->aux_stream);
   delete ctx->tables;
   delete ctx;
 }
@@ -540,7 +553,8 @@ extern "C" hack_status hack_score(hack_ctx* ctx, int32_t B, int32_t N_k, const v
   std::vector<ScoreItem> sitems;
   std::vector<int> groups;
   int item_keys = 0;
-  if (ctx->cfg.dtype == HACK_BF16) item_keys = plan_score_items(ctx, descs, list, &sitems, &groups);
+  const bool two_pass = ctx->score_mode == HACK_SCORE_TWO_PASS;
+  if (ctx->cfg.dtype == HACK_BF16) item_keys = plan_score_items(ctx, descs, list, two_pass, &sitems, &groups);
   Table t;
   const size_t o_desc = t.add(descs.data(), descs.size());
   const size_t o_list = t.add(list.data(), list.size());
@@ -549,7 +563,7 @@ extern "C" hack_status hack_score(hack_ctx* ctx, int32_t B, int32_t N_k, const v
   const uint8_t* dev;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
-  run_score(ctx, s, (const UnitDesc*)(dev + o_desc), (const int32_t*)(dev + o_list), (int)list.size(), max_t,
+  run_score(ctx, s, two_pass, ctx->rowstat, (const UnitDesc*)(dev + o_desc), (const int32_t*)(dev + o_list), (int)list.size(), max_t,
             (const ScoreItem*)(dev + o_sit), item_keys, groups, q, (const int32_t*)(dev + o_rows), n_obs, N_k, scale, in->k, k_new,
             importance, imp_stride);
   HIP_TRY(ctx, hipGetLastError());
@@ -891,14 +905,121 @@ extern "C" hack_status hack_kvcache_view(const hack_kvcache* c, hack_cache* view
   return HACK_OK;
 }
 
+namespace {
+
+// The units of a step that are launched together on one stream, with their launch tables.
+struct StepGroup {
+  std::vector<UnitDesc> descs;            // copies of the group's unit descriptors
+  std::vector<int32_t> comp, merging;     // indices into descs: units that compress / that also merge
+  int max_t = 0, max_rows = 0, merge_t = 0, merge_out = 0;
+  std::vector<AttnItem> items;
+  std::vector<ScoreItem> sitems;
+  std::vector<int> launches;
+  int item_keys = 0;
+  bool two_pass = false;
+  unsigned long long* slots = nullptr;    // row-sum exchange area of the group's score launches
+  const uint8_t* dev = nullptr;
+  size_t o_desc = 0, o_comp = 0, o_merge = 0, o_rows = 0, o_items = 0, o_sit = 0;
+  const UnitDesc* ddev() const { return reinterpret_cast<const UnitDesc*>(dev + o_desc); }
+};
+
+struct StepArgs {
+  int N_k, n_obs, tile;
+  bool split, fuse_append;
+  const void *q, *k_new, *v_new;
+  void* out;
+  float scale;
+  int32_t* kept;
+  int64_t kstride;
+  CachePtrs cp;
+  int32_t pos_new;
+};
+
+void add_unit(StepGroup* g, const UnitDesc& d, bool merges, int N_k) {
+  const int idx = (int)g->descs.size();
+  g->descs.push_back(d);
+  if (d.mode == MOVE_GATHER) {
+    g->comp.push_back(idx);
+    g->max_t = std::max(g->max_t, d.len_in + d.n_new);
+    g->max_rows = std::max(g->max_rows, d.n_out);
+    if (merges) {
+      g->merging.push_back(idx);
+      g->merge_t = std::max(g->merge_t, d.len_in + d.n_new);
+      g->merge_out = std::max(g->merge_out, d.n_out);
+    }
+  } else {
+    g->max_rows = std::max(g->max_rows, N_k);
+  }
+}
+
+hack_status upload_group(hack_ctx* ctx, StepGroup* g, const StepArgs& a, const int32_t* rows, hipStream_t s) {
+  build_attn_items(g->descs, a.N_k, a.tile, &g->items);
+  if (ctx->cfg.dtype == HACK_BF16 && !g->comp.empty())
+    g->item_keys = plan_score_items(ctx, g->descs, g->comp, g->two_pass, &g->sitems, &g->launches);
+  Table t;
+  g->o_desc = t.add(g->descs.data(), g->descs.size());
+  g->o_comp = t.add(g->comp.data(), g->comp.size());
+  g->o_merge = t.add(g->merging.data(), g->merging.size());
+  g->o_rows = t.add(rows, kMaxObs);
+  g->o_items = t.add(g->items.data(), g->items.size());
+  g->o_sit = t.add(g->sitems.data(), g->sitems.size());
+  return table_device(ctx, t, s, &g->dev);
+}
+
+// score -> select -> append / gather (-> merge) of a group's units
+void launch_chain(hack_ctx* ctx, const StepGroup& g, const StepArgs& a, hipStream_t s) {
+  const int32_t* comp_dev = reinterpret_cast<const int32_t*>(g.dev + g.o_comp);
+  if (!g.comp.empty()) {
+    run_score(ctx, s, g.two_pass, g.slots, g.ddev(), comp_dev, (int)g.comp.size(), g.max_t,
+              reinterpret_cast<const ScoreItem*>(g.dev + g.o_sit), g.item_keys, g.launches, a.q,
+              reinterpret_cast<const int32_t*>(g.dev + g.o_rows), a.n_obs, a.N_k, a.scale, a.cp.k, a.k_new, ctx->importance,
+              ctx->ws_stride);
+    launch_select(s, g.ddev(), comp_dev, (int)g.comp.size(), g.max_t, ctx->importance, ctx->ws_stride, a.kept, a.kstride);
+  }
+  if (!a.fuse_append)
+    launch_move(s, ctx->elem_bytes, ctx->cfg.head_dim, g.ddev(), (int)g.descs.size(), g.max_rows, a.cp, a.cp, a.k_new, a.v_new,
+                a.N_k, a.pos_new, a.kept, a.kstride);
+  if (!g.merging.empty())   // compression, the merge included, precedes the attention of the step
+    launch_merge(s, ctx->cfg.head_dim, g.ddev(), reinterpret_cast<const int32_t*>(g.dev + g.o_merge), (int)g.merging.size(),
+                 g.merge_t, g.merge_out, a.cp.k, a.cp.v, a.k_new, a.v_new, a.N_k, a.kept, a.kstride, a.cp.k, a.cp.v,
+                 ctx->merge_nn, ctx->merge_w, ctx->merge_inv, ctx->ws_stride);
+}
+
+void launch_group_attention(hack_ctx* ctx, const StepGroup& g, const StepArgs& a, hipStream_t s) {
+  const AttnItem* items = reinterpret_cast<const AttnItem*>(g.dev + g.o_items);
+  if (a.split)
+    launch_attn_split(s, ctx->cfg.head_dim, g.ddev(), items, (int)g.items.size(), a.q, a.cp.k, a.cp.v, a.k_new, a.v_new, a.cp.k,
+                      a.cp.v, a.cp.pos, a.pos_new, a.fuse_append ? 1 : 0, a.N_k, a.scale, a.out);
+  else
+    launch_attn(s, ctx->cfg.dtype, ctx->cfg.head_dim, g.ddev(), items, (int)g.items.size(), a.tile, a.q, a.cp.k, a.cp.v, a.N_k,
+                a.scale, a.out, ctx->attn_kernel);
+}
+
+}  // namespace
+
+// One scale step.  Units are independent, so a step may be issued as two groups: the compression chain
+// (score -> select -> gather) is a sequence of short, latency-bound launches that leaves most of the device
+// idle, while attention fills it.  With the overlap switched on (HACK_STEP_OVERLAP=1 when the context is
+// created), when contextual units compress at this step and other units exist, the others go first on the
+// caller's stream (their chain, then their attention, which is the longer one: structural budgets are the
+// larger), and the contextual units' chain and attention run beside that attention on a stream of the context,
+// forked and joined with events (capturable: a HIP graph gets two parallel branches).  The side chain scores
+// in the two-pass form, whose work-groups never wait for each other and can therefore share the device with
+// the attention launch.  What is computed per unit is the same; only the grouping of a unit's keys into work
+// items (chosen per launch) may differ from a single-group step.
+// The overlap is OFF by default: on MI355X it measured slower (1024^2 benchmark workload: 1005 against 841 us
+// per layer).  The attention launch of the first group holds every wave slot of the device, so the side chain
+// only advances as attention work-groups retire and ends with them; the second group's attention then runs
+// on its own, and a lone attention launch takes one work item's full latency (60 to 120 key blocks at half a
+// microsecond each) however few items it has.  Splitting a step therefore lengthens its critical path.
 static hack_status step_impl(hack_ctx* ctx, hack_kvcache* cache, int32_t B, int32_t N_k, const void* q,
                              const void* k_new, const void* v_new, const uint8_t* head_type,
                              const int32_t* budget, int32_t n_init, float scale, void* out,
                              int32_t* kept_idx_opt, int64_t idx_stride, hack_stream stream, bool final_merge) {
   hack_status st = check_common(ctx, B, N_k, true);
+  if (st != HACK_OK) return st;
   if (final_merge && ctx->cfg.dtype != HACK_BF16)
     return fail(ctx, HACK_EUNSUPPORTED, "the final-step merge is implemented for bf16 contexts");
-  if (st != HACK_OK) return st;
   const int U = B * ctx->cfg.heads, H = ctx->cfg.heads;
   if (!cache || cache->ctx != ctx || cache->n_units != U) return fail(ctx, HACK_EINVAL, "cache does not belong to this context / batch");
   if (!q || !k_new || !v_new || !head_type || !budget || !out) return fail(ctx, HACK_EINVAL, "NULL argument");
@@ -909,11 +1030,11 @@ static hack_status step_impl(hack_ctx* ctx, hack_kvcache* cache, int32_t B, int3
     if (head_type[h] > 1) return fail(ctx, HACK_EINVAL, "head_type[%d] = %d is not a head class", h, head_type[h]);
   if (cache->tokens_seen + N_k > INT32_MAX) return fail(ctx, HACK_ECAPACITY, "token ids overflow int32");
 
-  int32_t* kept = kept_idx_opt ? kept_idx_opt : ctx->kept;
-  const int64_t kstride = kept_idx_opt ? idx_stride : ctx->ws_stride;
+  StepArgs a{};
+  a.kept = kept_idx_opt ? kept_idx_opt : ctx->kept;
+  a.kstride = kept_idx_opt ? idx_stride : ctx->ws_stride;
   std::vector<UnitDesc> descs(U);
-  std::vector<int32_t> comp, merging;
-  int max_t = 0, max_rows = 0, merge_t = 0, merge_out = 0;
+  int n_comp = 0, n_side = 0;
   for (int u = 0; u < U; ++u) {
     const int L = cache->len[u];
     const int64_t T = (int64_t)L + N_k;
@@ -923,71 +1044,55 @@ static hack_status step_impl(hack_ctx* ctx, hack_kvcache* cache, int32_t B, int3
     if (budget[u] < T) {
       if (T > ctx->cfg.max_cache_len) return fail(ctx, HACK_ECAPACITY, "unit %d: T_in = %lld exceeds max_cache_len %d", u, (long long)T, ctx->cfg.max_cache_len);
       if (budget[u] > cache->cap[u]) return fail(ctx, HACK_ECAPACITY, "unit %d: budget %d exceeds its slab of %d rows", u, budget[u], cache->cap[u]);
-      if (budget[u] > kstride) return fail(ctx, HACK_ECAPACITY, "idx_stride %lld < budget[%d] = %d", (long long)kstride, u, budget[u]);
+      if (budget[u] > a.kstride) return fail(ctx, HACK_ECAPACITY, "idx_stride %lld < budget[%d] = %d", (long long)a.kstride, u, budget[u]);
       d.mode = MOVE_GATHER; d.n_out = budget[u]; d.out_off = cache->slab[cache->cur[u] ^ 1][u];
       plan_select(head_type[u % H], (int)T, budget[u], n_init, N_k, &d);
-      comp.push_back(u);
-      max_t = std::max(max_t, (int)T);
-      max_rows = std::max(max_rows, d.n_out);
-      if (final_merge && head_type[u % H] == HACK_CONTEXTUAL) {   // only f_C merges what it discards
-        merging.push_back(u);
-        merge_t = std::max(merge_t, (int)T);
-        merge_out = std::max(merge_out, d.n_out);
-      }
+      ++n_comp;
+      if (head_type[u % H] == HACK_CONTEXTUAL) ++n_side;
     } else {
       if (T > cache->cap[u]) return fail(ctx, HACK_ECAPACITY, "unit %d: %lld rows do not fit its slab of %d", u, (long long)T, cache->cap[u]);
       d.mode = MOVE_APPEND; d.n_out = (int)T; d.out_off = cache->off[u];
-      max_rows = std::max(max_rows, N_k);
     }
     descs[u] = d;
   }
-  const int n_obs = std::min(ctx->cfg.n_obs, N_k);
+  a.N_k = N_k;
+  a.n_obs = std::min(ctx->cfg.n_obs, N_k);
   int32_t rows[kMaxObs];
-  fill_q_rows(nullptr, n_obs, N_k, rows);
-  const bool split = use_split_attention(ctx, U, N_k);
-  const bool fuse_append = split && comp.empty();   // no unit compresses: the attention launch appends as well
-  const int tile = split ? attn_split_q_tile_rows() : attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim, U, N_k);
-  std::vector<AttnItem> items;
-  build_attn_items(descs, N_k, tile, &items);
+  fill_q_rows(nullptr, a.n_obs, N_k, rows);
+  a.split = use_split_attention(ctx, U, N_k);
+  a.fuse_append = a.split && n_comp == 0;   // no unit compresses: the attention launch appends as well
+  a.tile = a.split ? attn_split_q_tile_rows() : attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim, U, N_k);
+  a.q = q; a.k_new = k_new; a.v_new = v_new; a.out = out; a.scale = scale;
+  a.cp = CachePtrs{cache->k, cache->v, cache->pos};
+  a.pos_new = (int32_t)cache->tokens_seen;
 
-  std::vector<ScoreItem> sitems;
-  std::vector<int> groups;
-  int item_keys = 0;
-  if (ctx->cfg.dtype == HACK_BF16) item_keys = plan_score_items(ctx, descs, comp, &sitems, &groups);
-  Table t;
-  const size_t o_desc = t.add(descs.data(), descs.size());
-  const size_t o_comp = t.add(comp.data(), comp.size());
-  const size_t o_merge = t.add(merging.data(), merging.size());
-  const size_t o_rows = t.add(rows, kMaxObs);
-  const size_t o_items = t.add(items.data(), items.size());
-  const size_t o_sit = t.add(sitems.data(), sitems.size());
-  const uint8_t* dev;
-  hipStream_t s = static_cast<hipStream_t>(stream);
-  if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
-  const UnitDesc* ddev = (const UnitDesc*)(dev + o_desc);
-  CachePtrs cp{cache->k, cache->v, cache->pos};
-
-  if (!comp.empty()) {
-    run_score(ctx, s, ddev, (const int32_t*)(dev + o_comp), (int)comp.size(), max_t, (const ScoreItem*)(dev + o_sit),
-              item_keys, groups, q, (const int32_t*)(dev + o_rows), n_obs, N_k, scale, cache->k, k_new, ctx->importance,
-              ctx->ws_stride);
-    launch_select(s, ddev, (const int32_t*)(dev + o_comp), (int)comp.size(), max_t, ctx->importance, ctx->ws_stride, kept,
-                  kstride);
+  // group 0: the caller's stream; group 1 (optional): the compressing contextual units, beside group 0's attention
+  const bool two_groups = ctx->step_overlap && ctx->cfg.dtype == HACK_BF16 && n_side > 0 && n_side < U;
+  StepGroup g[2];
+  g[0].two_pass = ctx->score_mode == HACK_SCORE_TWO_PASS;
+  g[0].slots = ctx->rowstat;
+  g[1].two_pass = true;          // leaves its sums in the slots, hence an exchange area of its own
+  g[1].slots = ctx->rowstat_side;
+  for (int u = 0; u < U; ++u) {
+    const bool ctxl = head_type[u % H] == HACK_CONTEXTUAL, compresses = descs[u].mode == MOVE_GATHER;
+    add_unit(&g[two_groups && ctxl && compresses ? 1 : 0], descs[u], final_merge && ctxl && compresses, N_k);
   }
-  if (!fuse_append)
-    launch_move(s, ctx->elem_bytes, ctx->cfg.head_dim, ddev, U, max_rows, cp, cp, k_new, v_new, N_k,
-                (int32_t)cache->tokens_seen, kept, kstride);
-  if (!merging.empty())   // compression, the merge included, precedes the attention of the step
-    launch_merge(s, ctx->cfg.head_dim, ddev, (const int32_t*)(dev + o_merge), (int)merging.size(), merge_t, merge_out,
-                 cache->k, cache->v, k_new, v_new, N_k, kept, kstride, cache->k, cache->v, ctx->merge_nn, ctx->merge_w,
-                 ctx->merge_inv, ctx->ws_stride);
-  if (split)
-    launch_attn_split(s, ctx->cfg.head_dim, ddev, (const AttnItem*)(dev + o_items), (int)items.size(), q, cache->k,
-                      cache->v, k_new, v_new, cache->k, cache->v, cache->pos, (int32_t)cache->tokens_seen,
-                      fuse_append ? 1 : 0, N_k, scale, out);
-  else
-    launch_attn(s, ctx->cfg.dtype, ctx->cfg.head_dim, ddev, (const AttnItem*)(dev + o_items), (int)items.size(), tile,
-                q, cache->k, cache->v, N_k, scale, out, ctx->attn_kernel);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if ((st = upload_group(ctx, &g[0], a, rows, s)) != HACK_OK) return st;
+  if (two_groups && (st = upload_group(ctx, &g[1], a, rows, s)) != HACK_OK) return st;
+
+  launch_chain(ctx, g[0], a, s);
+  if (two_groups) {
+    HIP_TRY(ctx, hipEventRecord(ctx->ev_fork, s));
+    HIP_TRY(ctx, hipStreamWaitEvent(ctx->aux_stream, ctx->ev_fork, 0));
+  }
+  launch_group_attention(ctx, g[0], a, s);
+  if (two_groups) {
+    launch_chain(ctx, g[1], a, ctx->aux_stream);
+    launch_group_attention(ctx, g[1], a, ctx->aux_stream);
+    HIP_TRY(ctx, hipEventRecord(ctx->ev_join, ctx->aux_stream));
+    HIP_TRY(ctx, hipStreamWaitEvent(s, ctx->ev_join, 0));
+  }
   HIP_TRY(ctx, hipGetLastError());
 
   for (int u = 0; u < U; ++u) {

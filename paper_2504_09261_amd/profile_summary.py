@@ -3,12 +3,15 @@
     python3 -m paper_2504_09261_amd.profile_summary stats    <..._kernel_stats.csv>
     python3 -m paper_2504_09261_amd.profile_summary counters <..._counter_collection.csv>
             [--calib <copy run's ..._counter_collection.csv> --calib-bytes N --calib-kernel SUBSTR]
+            [--trace <the same run's ..._kernel_trace.csv>]
 
 `stats` lists calls / average / min / max duration per kernel.  `counters` lists,
 per kernel, the mean of every collected counter per dispatch; with --calib the
 same counter's mean over the dispatches of a plain copy kernel that is known to
 read and write N bytes gives the bytes-per-count factor that is applied to the
-FETCH_SIZE / WRITE_SIZE rows.
+FETCH_SIZE / WRITE_SIZE rows.  With --trace the mean duration of every kernel's
+dispatches in the same run is listed too (a counter that ticks once per clock,
+divided by that duration, gives the clock the kernel ran at).
 """
 from __future__ import annotations
 
@@ -43,6 +46,15 @@ def counter_means(path: str):
     return acc
 
 
+def durations(path: str) -> None:
+    acc = collections.defaultdict(list)
+    for r in csv.DictReader(open(path)):
+        acc[short(r["Kernel_Name"])].append(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]))
+    print(f"{'kernel':72s} {'dispatches':>10s} {'mean_duration_us':>18s}")
+    for kern, v in sorted(acc.items()):
+        print(f"{kern:72s} {len(v):10d} {sum(v) / len(v) / 1e3:18.2f}")
+
+
 def counters(path: str, calib: str | None, calib_bytes: int, calib_kernel: str) -> None:
     factor = {}
     if calib:
@@ -68,11 +80,14 @@ def main() -> None:
     ap.add_argument("--calib")
     ap.add_argument("--calib-bytes", type=int, default=0)
     ap.add_argument("--calib-kernel", default="UnaryFunctor")
+    ap.add_argument("--trace")
     a = ap.parse_args()
     if a.what == "stats":
         stats(a.csv)
     else:
         counters(a.csv, a.calib, a.calib_bytes, a.calib_kernel)
+        if a.trace:
+            durations(a.trace)
 
 
 if __name__ == "__main__":

@@ -223,6 +223,59 @@ def test_schedule_with_either_attention_kernel_forced(attention):
     assert stats["mismatch"] == 0 and stats["compress_events"] > 0
 
 
+def test_schedule_with_the_step_overlap_switched_on(monkeypatch):
+    """hack_step can issue a step as two groups of units on two streams (the contextual units' compression
+    chain and attention beside the others' attention, forked and joined with events).  It is off by default;
+    switched on, whole schedules must match the oracle all the same, eagerly and from a captured graph."""
+    u = _u()
+    monkeypatch.setenv("HACK_STEP_OVERLAP", "1")
+    cfg = wl.get_config(1, batch=2)
+    stats = run_free(cfg, 1, list(range(0, cfg.n_units, 4)))
+    assert stats["mismatch"] == 0 and stats["compress_events"] > 0
+    cfg = wl.get_config(2)
+    types = wl.head_types(cfg, 0)
+    units = [int(np.where(types == 0)[0][2]), int(np.where(types == 1)[0][2]), cfg.heads + int(np.where(types == 0)[0][3])]
+    stats = run_free(cfg, 0, units, final_merge=True)
+    assert stats["mismatch"] == 0 and stats["compress_events"] >= 11
+    # captured: two parallel branches per compressing step, replayed twice against the eager outputs
+    cfg = wl.get_config(1, batch=2)
+    hk = u.make_hack(cfg)
+    types = wl.head_types(cfg, 0)
+    mc = hk.managed_cache(np.minimum(np.tile(wl.head_budgets(cfg, 0), cfg.batch), cfg.T_K))
+    data = wl.gen_layer(cfg, 0)
+    budgets = [wl.step_budgets(cfg, 0, k) for k in range(1, cfg.n_steps + 1)]
+    q = [u.to_dev(data[k].q, cfg.dtype) for k in range(1, cfg.n_steps + 1)]
+    kn = [u.to_dev(data[k].k, cfg.dtype) for k in range(1, cfg.n_steps + 1)]
+    vn = [u.to_dev(data[k].v, cfg.dtype) for k in range(1, cfg.n_steps + 1)]
+    out = [torch.zeros_like(x) for x in q]
+
+    def run():
+        mc.reset()
+        for i in range(cfg.n_steps):
+            hk.step(mc, q[i], kn[i], vn[i], types, budgets[i], cfg.n_init, cfg.scale, out[i])
+
+    run()
+    torch.cuda.synchronize()
+    ref = [o.clone() for o in out]
+    st = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(st):
+        with torch.cuda.graph(g, stream=st):
+            run()
+    for rep in range(2):
+        for o in out:
+            o.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(st):
+            g.replay()
+        torch.cuda.synchronize()
+        hk.check()
+        for a, b in zip(ref, out):
+            assert torch.equal(a, b), rep
+    mc.close()
+    hk.close()
+
+
 def test_schedule_on_a_cache_without_position_ids():
     """The token-id array of the managed cache is optional: appends (fused into the attention
     launch or separate) and gathers must leave it alone when it is absent."""
