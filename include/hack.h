@@ -23,6 +23,11 @@
  *  - Arguments are validated on the host before anything is launched; on error
  *    nothing has been launched.
  *  - A context serves one stream at a time (its workspace is shared by calls).
+ *    It owns a second stream and two events, used only by hack_step when the
+ *    two-group overlap is switched on (environment HACK_STEP_OVERLAP=1 when the
+ *    context is created; off by default): the side work is forked from and
+ *    joined back into the caller's stream inside the call, so callers, and
+ *    stream captures, see one stream either way.
  *  - Small per-call launch tables (offsets, lengths, work lists) are uploaded
  *    the first time a particular table is seen and reused afterwards, so a
  *    repeated schedule issues kernel launches only and can be captured in a

@@ -595,9 +595,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
     constexpr bool FIRST = decltype(first_tag)::value;
     constexpr bool LAST = decltype(last_tag)::value;
     constexpr bool STEADY = decltype(steady_tag)::value;
-    // K(b+1) and V(b-1) have landed: everything but the two copy groups issued one stage ago
-    if (STEADY) dma_wait_but<2 * IPW>();
-    else dma_wait_but<0>();
+    // K(b+1) and V(b-1) have landed: everything but what the previous stage issued, which is V(b) and, if that
+    // block exists, K(b+2) (short caches never reach the steady loop: waiting for everything there would put a
+    // whole memory latency into every stage)
+    if (STEADY || b + 2 < n_blocks) dma_wait_but<2 * IPW>();
+    else dma_wait_but<IPW>();
     __syncthreads();   // both are visible to every wave; the slots of K(b) and V(b-2) are free
     if (STEADY || b + 3 < n_blocks) issue_k(b + 3, S, STEADY);
     if (STEADY || b + 1 < n_blocks) issue_v(b + 1, (S + 1) % NS, STEADY);

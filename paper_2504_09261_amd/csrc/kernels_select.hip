@@ -16,8 +16,12 @@ namespace hack {
 
 namespace {
 
-constexpr int kThreads = 1024;
-constexpr int kWaves = kThreads / 64;
+// Work-group size: 1024 threads for long units, 256 for short ones (template parameter).  A unit of a few
+// hundred keys leaves most of 1024 threads idle at every barrier, and a launch over many short units (the
+// 256^2 schedules: hundreds of units of at most ~600 keys) then needs several rounds of work-groups.
+constexpr int kThreadsLong = 1024;
+constexpr int kThreadsShort = 256;
+constexpr int kShortMaxKeys = 1024;   // units up to this many keys take the short form
 
 __device__ __forceinline__ uint32_t orderable(float f) {
   uint32_t u = __float_as_uint(f);
@@ -35,6 +39,7 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
 }
 
 // Exclusive prefix of v over the work-group in thread order; total to all threads.
+template <int kWaves>
 __device__ __forceinline__ int block_exclusive_scan(int v, int* wave_tot, int& total) {
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int incl = wave_inclusive_scan(v);
@@ -52,10 +57,12 @@ __device__ __forceinline__ int block_exclusive_scan(int v, int* wave_tot, int& t
   return base + incl - v;
 }
 
+template <int kThreads>
 __global__ __launch_bounds__(kThreads) void select_kernel(
     const UnitDesc* __restrict__ descs, const int32_t* __restrict__ list,
     const float* __restrict__ importance, int64_t imp_stride, int32_t* __restrict__ kept_idx,
     int64_t idx_stride) {
+  constexpr int kWaves = kThreads / 64;
   extern __shared__ uint32_t keys[];  // ranked segment as orderable keys
   __shared__ uint32_t hist[256];
   __shared__ int wave_tot[kWaves];
@@ -149,7 +156,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
     const int a = max(j0, d.sel_lo), b = min(j1, d.sel_hi);
     for (int j = a; j < b; ++j) n_eq += (keys[j - d.sel_lo] == tau);
     int tot_eq;
-    eq_rank = block_exclusive_scan(n_eq, wave_tot, tot_eq);
+    eq_rank = block_exclusive_scan<kWaves>(n_eq, wave_tot, tot_eq);
   }
 
   auto kept = [&](int j, int& eq_seen) -> bool {
@@ -166,7 +173,7 @@ __global__ __launch_bounds__(kThreads) void select_kernel(
   int cnt = 0, e = eq_rank;
   for (int j = j0; j < j1; ++j) cnt += kept(j, e) ? 1 : 0;
   int total;
-  int pos = block_exclusive_scan(cnt, wave_tot, total);
+  int pos = block_exclusive_scan<kWaves>(cnt, wave_tot, total);
   e = eq_rank;
   for (int j = j0; j < j1; ++j)
     if (kept(j, e)) out[pos++] = j;
@@ -190,14 +197,18 @@ void launch_select(hipStream_t s, const UnitDesc* descs, const int32_t* list, in
     if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < 64) {
       std::lock_guard<std::mutex> lock(mu);
       if (!configured[dev]) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel<kThreadsLong>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)select_lds_bytes(32768));
         configured[dev] = true;
       }
     }
   }
-  hipLaunchKernelGGL(select_kernel, dim3(n_list), dim3(kThreads), lds, s, descs, list, importance,
-                     imp_stride, kept_idx, idx_stride);
+  if (max_t_in <= kShortMaxKeys)
+    hipLaunchKernelGGL(select_kernel<kThreadsShort>, dim3(n_list), dim3(kThreadsShort), lds, s, descs, list, importance,
+                       imp_stride, kept_idx, idx_stride);
+  else
+    hipLaunchKernelGGL(select_kernel<kThreadsLong>, dim3(n_list), dim3(kThreadsLong), lds, s, descs, list, importance,
+                       imp_stride, kept_idx, idx_stride);
 }
 
 }  // namespace hack
