@@ -19,7 +19,7 @@ DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang"
 # The score kernels read every MFMA result with the vector ALU straight away:
 # keeping the accumulators in VGPRs spares one AGPR copy per result register.
 PER_SOURCE = {"kernels_score.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
-COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option",
+COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-unknown-warning-option", "-Wno-inline-asm",
           "-Wno-unused-command-line-argument"]
 
 

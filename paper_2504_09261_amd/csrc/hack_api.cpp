@@ -82,6 +82,12 @@ struct hack_ctx {
   int score_capacity[4] = {0, 0, 0, 0};   // bf16 path: score items one fused launch may hold (resident waves) for items of 32, 64, 128, 256 keys
   int split_max_items = 0;       // launches with at most this many 32-query attention items use the key-split kernel
   int attn_kernel = 1;           // bf16 kernel of the 128-query items: 1 = deeper pipeline, 0 = plain (HACK_ATTN_PIPE=0)
+  // streamed form of that kernel: the launch is cut into equal runs of key blocks, one per resident work-group
+  int attn_stream = 0;           // 0: off (default, see use_stream_attention), 1: every launch of the 128-query kernel, 2: A/B aid (HACK_ATTN_STREAM)
+  int attn_slots = 0;            // work-groups of the streamed kernel the device holds at once
+  float* part_o = nullptr;       // [2 * attn_slots, 128, head_dim] unnormalised partial outputs
+  float* part_ml = nullptr;      // [2 * attn_slots, 2, 128] their references and normalisers
+  unsigned* part_count = nullptr; // [attn_slots] ticket counters, zero between launches
   // hack_step overlap: the compression chain of one group of units runs beside the attention of the other group
   bool step_overlap = false;     // off by default (measured slower on MI355X, see step_impl); HACK_STEP_OVERLAP=1 switches it on
   hipStream_t aux_stream = nullptr;
@@ -289,6 +295,49 @@ bool use_split_attention(const hack_ctx* ctx, int n_units, int N_k) {
   return (int64_t)n_units * ((N_k + tile - 1) / tile) <= ctx->split_max_items;
 }
 
+// The 128-query bf16 kernel in its streamed form: the work items of the launch are cut into one run of
+// key blocks per resident work-group (plan_attn_stream), so that every work-group holds the same number of
+// blocks whatever the number and the lengths of the work items are; work items that a cut falls into are
+// put together from partial results.  OFF by default (HACK_ATTN_STREAM=1 when the context is created
+// switches it on for every launch of the 128-query kernel): on MI355X it measured slower than one work
+// item per work-group on all but one step of the benchmark workloads (1024^2 schedules, scale steps 9-13,
+// us per launch, plain / streamed: 16 heads x batch 2: 34 / 39, 56 / 64, 113 / 104, 136 / 140, 222 / 230;
+// 32 heads x batch 2: 51 / 54, 74 / 92, 159 / 175, 253 / 270, 425 / 527).  In-kernel time stamps show why:
+// of the two work-groups that share a compute unit the older one is served first and runs the steady
+// loop at 0.73-0.76 us per key block, the younger one at 0.97-1.0 (0.55 alone), so equal shares finish
+// up to 30 % apart and the launch lasts as long as the slowest; the hardware's own dispatch of whole work
+// items absorbs that difference.  On top come about 3 us per extra segment (pipeline fill), 3-4 us per
+// partial result written and 3-4 us per part added up.
+// `shared` says that another attention launch of the context may run at the same time (the partial-result
+// arrays are the context's), which rules the streamed form out.
+constexpr int kStreamOverheadBlocks = 4;   // start and end of a segment, in key blocks of the steady loop
+constexpr int kStreamMinBlocks = 4;        // shortest segment a work item is cut into
+bool use_stream_attention(const hack_ctx* ctx, const std::vector<UnitDesc>& descs, int N_k, bool shared, AttnStreamPlan* plan) {
+  if (ctx->cfg.dtype != HACK_BF16 || ctx->attn_kernel == 0 || ctx->attn_stream <= 0 || ctx->attn_slots <= 0 || shared) return false;
+  if (descs.empty()) return false;
+  const int tile = attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim, (int)descs.size(), N_k);
+  if (tile != 128) return false;
+  std::vector<int32_t> n_keys(descs.size());
+  for (size_t i = 0; i < descs.size(); ++i) n_keys[i] = descs[i].n_out;
+  if (ctx->attn_stream == 2) {
+    // A/B aid: the streamed kernel on uncut work items, one per work-group, in the order of the plain launch
+    std::vector<AttnItem> items;
+    build_attn_items(descs, N_k, tile, &items);
+    plan->segs.clear();
+    plan->seg_begin.assign(1, 0);
+    for (const AttnItem& it : items) {
+      if (it.desc >= 0) plan->segs.push_back(AttnSeg{it.desc, it.q_tile, 0, 0x3fffffff, -1, 0, 0, 0});
+      plan->seg_begin.push_back((int32_t)plan->segs.size());
+    }
+    plan->n_groups = (int)items.size();
+    plan->n_parts = plan->n_counters = 0;
+    return plan->n_groups > 0;
+  }
+  plan_attn_stream(n_keys.data(), (int)descs.size(), (N_k + tile - 1) / tile, ctx->attn_slots, kStreamOverheadBlocks,
+                   kStreamMinBlocks, plan);
+  return plan->n_groups > 0 && plan->n_parts <= 2 * ctx->attn_slots && plan->n_counters <= ctx->attn_slots;
+}
+
 int finish_score_plan(const hack_ctx* ctx, const std::vector<UnitDesc>& descs, const std::vector<int32_t>& list, int keys,
                       bool two_pass, std::vector<ScoreItem>* items, std::vector<int>* group_begin);
 
@@ -445,6 +494,7 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (const char* v = std::getenv("HACK_ATTN_SPLIT_ITEMS")) ctx->split_max_items = std::atoi(v);   // tuning / test override
   if (const char* v = std::getenv("HACK_STEP_OVERLAP")) ctx->step_overlap = std::atoi(v) != 0;
   if (const char* v = std::getenv("HACK_ATTN_PIPE")) ctx->attn_kernel = std::atoi(v) != 0;   // A/B and test override
+  if (const char* v = std::getenv("HACK_ATTN_STREAM")) ctx->attn_stream = std::atoi(v);       // A/B and test override
   hipError_t e = hipSetDevice(cfg->device);
   const size_t n_ws = (size_t)cfg->max_units * ctx->ws_stride;
   if (e == hipSuccess) e = hipMalloc((void**)&ctx->importance, n_ws * sizeof(float));
@@ -464,6 +514,14 @@ extern "C" hack_status hack_create(hack_ctx** out, const hack_config* cfg) {
   if (e == hipSuccess && cfg->dtype == HACK_BF16) e = hipMalloc((void**)&ctx->merge_nn, n_ws * sizeof(int32_t));
   if (e == hipSuccess && cfg->dtype == HACK_BF16) e = hipMalloc((void**)&ctx->merge_w, n_ws * sizeof(float));
   if (e == hipSuccess && cfg->dtype == HACK_BF16) e = hipMalloc((void**)&ctx->merge_inv, n_ws * sizeof(float));
+  if (e == hipSuccess && cfg->dtype == HACK_BF16) {
+    ctx->attn_slots = attn_stream_slots(cfg->head_dim);
+    const size_t n_part = 2 * (size_t)std::max(ctx->attn_slots, 1);
+    e = hipMalloc((void**)&ctx->part_o, n_part * 128 * cfg->head_dim * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->part_ml, n_part * 256 * sizeof(float));
+    if (e == hipSuccess) e = hipMalloc((void**)&ctx->part_count, (n_part / 2) * sizeof(unsigned));
+    if (e == hipSuccess) e = hipMemset(ctx->part_count, 0, (n_part / 2) * sizeof(unsigned));
+  }
   if (e == hipSuccess) e = hipHostMalloc((void**)&ctx->fault, 2 * sizeof(int), hipHostMallocDefault);
   if (e == hipSuccess) ctx->fault[0] = ctx->fault[1] = 0;
   if (e == hipSuccess) e = hipMemset(ctx->rowstat, 0xFF, n_slots * sizeof(unsigned long long));   // every slot empty
@@ -505,6 +563,9 @@ extern "C" void hack_destroy(hack_ctx* ctx) {
   if (ctx->merge_nn) (void)hipFree(ctx->merge_nn);
   if (ctx->merge_w) (void)hipFree(ctx->merge_w);
   if (ctx->merge_inv) (void)hipFree(ctx->merge_inv);
+  if (ctx->part_o) (void)hipFree(ctx->part_o);
+  if (ctx->part_ml) (void)hipFree(ctx->part_ml);
+  if (ctx->part_count) (void)hipFree(ctx->part_count);
   if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
   if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
   if (ctx->aux_stream) (void)hipStreamDestroy(ctx->aux_stream);
@@ -790,14 +851,22 @@ extern "C" hack_status hack_attn(hack_ctx* ctx, int32_t B, int32_t N_k, const vo
   const bool split = use_split_attention(ctx, U, N_k);
   const int tile = split ? attn_split_q_tile_rows() : attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim, U, N_k);
   std::vector<AttnItem> items;
-  build_attn_items(descs, N_k, tile, &items);
+  AttnStreamPlan plan;
+  const bool streamed = !split && use_stream_attention(ctx, descs, N_k, false, &plan);
+  if (!streamed) build_attn_items(descs, N_k, tile, &items);
   Table t;
   const size_t o_desc = t.add(descs.data(), descs.size());
   const size_t o_items = t.add(items.data(), items.size());
+  const size_t o_segs = t.add(plan.segs.data(), plan.segs.size());
+  const size_t o_segb = t.add(plan.seg_begin.data(), plan.seg_begin.size());
   const uint8_t* dev;
   hipStream_t s = static_cast<hipStream_t>(stream);
   if ((st = table_device(ctx, t, s, &dev)) != HACK_OK) return st;
-  if (split)
+  if (streamed)
+    launch_attn_stream(s, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), (const AttnSeg*)(dev + o_segs),
+                       (const int32_t*)(dev + o_segb), plan.n_groups, q, kv->k, kv->v, N_k, scale, out, ctx->part_o,
+                       ctx->part_ml, ctx->part_count);
+  else if (split)
     launch_attn_split(s, ctx->cfg.head_dim, (const UnitDesc*)(dev + o_desc), (const AttnItem*)(dev + o_items),
                       (int)items.size(), q, kv->k, kv->v, nullptr, nullptr, nullptr, nullptr, nullptr, 0, 0, N_k, scale,
                       out);
@@ -913,19 +982,21 @@ struct StepGroup {
   std::vector<int32_t> comp, merging;     // indices into descs: units that compress / that also merge
   int max_t = 0, max_rows = 0, merge_t = 0, merge_out = 0;
   std::vector<AttnItem> items;
+  AttnStreamPlan plan;                    // attention in the streamed form (then `items` stays empty)
+  bool streamed = false;
   std::vector<ScoreItem> sitems;
   std::vector<int> launches;
   int item_keys = 0;
   bool two_pass = false;
   unsigned long long* slots = nullptr;    // row-sum exchange area of the group's score launches
   const uint8_t* dev = nullptr;
-  size_t o_desc = 0, o_comp = 0, o_merge = 0, o_rows = 0, o_items = 0, o_sit = 0;
+  size_t o_desc = 0, o_comp = 0, o_merge = 0, o_rows = 0, o_items = 0, o_sit = 0, o_segs = 0, o_segb = 0;
   const UnitDesc* ddev() const { return reinterpret_cast<const UnitDesc*>(dev + o_desc); }
 };
 
 struct StepArgs {
   int N_k, n_obs, tile;
-  bool split, fuse_append;
+  bool split, fuse_append, shared;   // shared: two groups of the step may attend at the same time
   const void *q, *k_new, *v_new;
   void* out;
   float scale;
@@ -953,7 +1024,8 @@ void add_unit(StepGroup* g, const UnitDesc& d, bool merges, int N_k) {
 }
 
 hack_status upload_group(hack_ctx* ctx, StepGroup* g, const StepArgs& a, const int32_t* rows, hipStream_t s) {
-  build_attn_items(g->descs, a.N_k, a.tile, &g->items);
+  g->streamed = !a.split && use_stream_attention(ctx, g->descs, a.N_k, a.shared, &g->plan);
+  if (!g->streamed) build_attn_items(g->descs, a.N_k, a.tile, &g->items);
   if (ctx->cfg.dtype == HACK_BF16 && !g->comp.empty())
     g->item_keys = plan_score_items(ctx, g->descs, g->comp, g->two_pass, &g->sitems, &g->launches);
   Table t;
@@ -963,6 +1035,8 @@ hack_status upload_group(hack_ctx* ctx, StepGroup* g, const StepArgs& a, const i
   g->o_rows = t.add(rows, kMaxObs);
   g->o_items = t.add(g->items.data(), g->items.size());
   g->o_sit = t.add(g->sitems.data(), g->sitems.size());
+  g->o_segs = t.add(g->plan.segs.data(), g->plan.segs.size());
+  g->o_segb = t.add(g->plan.seg_begin.data(), g->plan.seg_begin.size());
   return table_device(ctx, t, s, &g->dev);
 }
 
@@ -987,7 +1061,11 @@ void launch_chain(hack_ctx* ctx, const StepGroup& g, const StepArgs& a, hipStrea
 
 void launch_group_attention(hack_ctx* ctx, const StepGroup& g, const StepArgs& a, hipStream_t s) {
   const AttnItem* items = reinterpret_cast<const AttnItem*>(g.dev + g.o_items);
-  if (a.split)
+  if (g.streamed)
+    launch_attn_stream(s, ctx->cfg.head_dim, g.ddev(), reinterpret_cast<const AttnSeg*>(g.dev + g.o_segs),
+                       reinterpret_cast<const int32_t*>(g.dev + g.o_segb), g.plan.n_groups, a.q, a.cp.k, a.cp.v, a.N_k, a.scale,
+                       a.out, ctx->part_o, ctx->part_ml, ctx->part_count);
+  else if (a.split)
     launch_attn_split(s, ctx->cfg.head_dim, g.ddev(), items, (int)g.items.size(), a.q, a.cp.k, a.cp.v, a.k_new, a.v_new, a.cp.k,
                       a.cp.v, a.cp.pos, a.pos_new, a.fuse_append ? 1 : 0, a.N_k, a.scale, a.out);
   else
@@ -1068,6 +1146,7 @@ static hack_status step_impl(hack_ctx* ctx, hack_kvcache* cache, int32_t B, int3
 
   // group 0: the caller's stream; group 1 (optional): the compressing contextual units, beside group 0's attention
   const bool two_groups = ctx->step_overlap && ctx->cfg.dtype == HACK_BF16 && n_side > 0 && n_side < U;
+  a.shared = two_groups;
   StepGroup g[2];
   g[0].two_pass = ctx->score_mode == HACK_SCORE_TWO_PASS;
   g[0].slots = ctx->rowstat;

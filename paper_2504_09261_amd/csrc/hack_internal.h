@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "attn_plan.h"
+
 namespace hack {
 
 // Per-unit launch table entry, built on the host from the caller's host arrays
@@ -128,6 +130,13 @@ size_t select_lds_bytes(int max_t_in);
 void launch_attn(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, const AttnItem* items,
                  int n_items, int q_tile_rows, const void* q, const void* k_cache,
                  const void* v_cache, int N_k, float scale, void* out, int bf16_kernel);
+// Streamed form of the 128-query bf16 kernel: work-group i serves segs[seg_begin[i] .. seg_begin[i+1]).
+// part_o: n_slots * 128 * head_dim floats, part_ml: n_slots * 256 floats, part_count: one zeroed
+// counter per cut work item (left zero).  Launches that share these arrays must not overlap.
+int attn_stream_slots(int head_dim);   // work-groups the current device holds at once
+void launch_attn_stream(hipStream_t s, int head_dim, const UnitDesc* descs, const AttnSeg* segs, const int32_t* seg_begin,
+                        int n_groups, const void* q, const void* k_cache, const void* v_cache, int N_k, float scale,
+                        void* out, float* part_o, float* part_ml, unsigned* part_count);
 // bf16 attention for steps with few queries: work item = (unit, tile of
 // attn_split_q_tile_rows() queries), keys split over the waves of a work-group.
 // fuse == 0: attends over rows [out_off, out_off + n_out) of k_cache / v_cache.

@@ -429,12 +429,24 @@ __device__ __forceinline__ void sched_interleave() {
   }
 }
 
-template <int D, int NW>
+// STREAM = false: work-group i serves work item items[i] (one query tile of one unit, all of its keys).
+// STREAM = true: work-group i serves the segments segs[seg_begin[i] .. seg_begin[i+1]), one after the
+// other.  A segment is a run of 32-key blocks [blk0, blk1) of one work item; the host cuts the
+// concatenation of all work items of a launch into as many equal runs as the device holds work-groups
+// at once, so every work-group gets the same number of blocks whatever the lengths of the units are.
+// A segment that covers its work item completely stores the output rows as usual (part < 0).
+// Otherwise it leaves its reference, normaliser and unnormalised O^T (float32) in slot `part` of the
+// partial-result arrays and draws a ticket from the work item's counter; the work-group that draws
+// the last of the item's n_parts tickets (every other part has been stored and published by then)
+// adds the parts first_part .. first_part + n_parts - 1 up and stores the output rows, then leaves the
+// counter at zero for the next launch.  Nobody waits for anybody.
+template <int D, int NW, bool STREAM>
 __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
     const UnitDesc* __restrict__ descs, const AttnItem* __restrict__ items,
+    const AttnSeg* __restrict__ segs, const int32_t* __restrict__ seg_begin,
     const __bf16* __restrict__ q, const __bf16* __restrict__ k_cache,
     const __bf16* __restrict__ v_cache, int N_k, float scale,
-    __bf16* __restrict__ out) {
+    __bf16* __restrict__ out, float* part_o, float* part_ml, unsigned* part_count) {
   constexpr int KK = D / 16;        // MFMA steps over head_dim for S^T
   constexpr int MB = D / 32;        // 32-row blocks of O^T
   constexpr int CPR = D / 8;        // 16-byte chunks per row
@@ -445,22 +457,41 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
   static_assert(IPW >= 1, "a block must give every wave at least one copy instruction");
   static_assert(KK == 2 * MB, "as many score MFMAs as PV MFMAs per block");
 
-  const AttnItem it = items[blockIdx.x];
-  if (it.desc < 0) return;
-  const UnitDesc d = descs[it.desc];
-  const int len = d.n_out;
-  const int tid = threadIdx.x, lane = tid & 63;
+  const int tid = threadIdx.x;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int col = lane & 31, half = lane >> 5;
 
   __shared__ __attribute__((aligned(1024))) __bf16 Ks[NS][BLK];
   __shared__ __attribute__((aligned(1024))) __bf16 Vs[NS][BLK];
+  __shared__ int last_ticket;
 
-  const __bf16* kg = k_cache + d.out_off * D;
-  const __bf16* vg = v_cache + d.out_off * D;
+  int seg_lo = blockIdx.x, seg_hi = blockIdx.x + 1;
+  if (STREAM) {
+    seg_lo = seg_begin[blockIdx.x];
+    seg_hi = seg_begin[blockIdx.x + 1];
+  }
+  for (int si = seg_lo; si < seg_hi; ++si) {
+  // The lane index is re-read per segment behind a compiler barrier: values derived from it that
+  // only the ragged paths need are then formed where they are used instead of being carried
+  // through the main loop in registers.
+  int lane = tid & 63;
+  if (STREAM) asm volatile("" : "+v"(lane));
+  const int col = lane & 31, half = lane >> 5;
+  AttnSeg sg;
+  if (STREAM) {
+    sg = segs[si];
+  } else {
+    const AttnItem it = items[si];
+    if (it.desc < 0) return;
+    sg = AttnSeg{it.desc, it.q_tile, 0, 0x3fffffff, -1, 0, 0, 0};
+  }
+  const UnitDesc d = descs[sg.desc];
+  const int key0 = sg.blk0 * kKB;                                               // first key of the segment
+  const int len = (int)min((int64_t)sg.blk1 * kKB, (int64_t)d.n_out) - key0;    // its keys
+
+  const __bf16* kg = k_cache + (d.out_off + key0) * D;
+  const __bf16* vg = v_cache + (d.out_off + key0) * D;
   const int n_blocks = (len + kKB - 1) / kKB;
   const int n_full = len / kKB;
-
   unsigned k_src[IPW], v_src[IPW];
 #pragma unroll
   for (int i = 0; i < IPW; ++i) {
@@ -499,7 +530,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
   issue_v(0, 0);
 
   // Q fragments (B operand of S^T = K Q^T): query col, head-dim slice [16kk + 8h, +8).
-  const int q0 = it.q_tile * (NW * 32) + w * 32;
+  const int q0 = sg.q_tile * (NW * 32) + w * 32;
   bf16x8 qf[KK];
   {
     const int qi = min(q0 + col, N_k - 1);
@@ -683,10 +714,74 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
   }
 
   // ---- normalise and store: lane holds query col, head-dim rows 32mb + 8(r/4) + 4h + r%4 ----
-  const float l = pair_sum(l_run);
+  float l = pair_sum(l_run);
+  bool store = true;
+  if (STREAM && sg.part >= 0) {
+    // Partial result, register-major (every store instruction of a wave writes 512 contiguous bytes).
+    // The parts of a work item come from work-groups on different XCDs, whose L2 caches are not kept
+    // coherent with each other, so parts and tickets travel as device-scope relaxed atomics (stores
+    // that write through, loads that do not take a stale line), 8 bytes each; a device-scope fence
+    // would instead write back and invalidate the whole L2 at every segment end.  Order is kept by
+    // hand: a work-group draws its ticket only after every store of its part has been acknowledged.
+    constexpr int QT = NW * 32;
+    typedef unsigned long long u64;
+    auto pack2 = [](float a, float b) -> u64 {
+      return (u64)__builtin_bit_cast(unsigned, a) | ((u64)__builtin_bit_cast(unsigned, b) << 32);
+    };
+    {
+      u64* po = reinterpret_cast<u64*>(part_o + (int64_t)sg.part * (QT * D)) + (w * MB * 8) * 64 + lane;
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int h2 = 0; h2 < 8; ++h2)
+          __hip_atomic_store(po + (mb * 8 + h2) * 64, pack2(o[mb][2 * h2], o[mb][2 * h2 + 1]), __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+      if (half == 0)   // reference in log2 units (finite: the segment holds a valid key) and normaliser
+        __hip_atomic_store(reinterpret_cast<u64*>(part_ml + (int64_t)sg.part * (2 * QT)) + w * 32 + col, pack2(mc, l),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's stores have been acknowledged
+    __syncthreads();                                    // ... and so have the whole work-group's
+    if (tid == 0)
+      last_ticket = (__hip_atomic_fetch_add(&part_count[sg.counter], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+                     (unsigned)(sg.n_parts - 1)) ? 1 : 0;
+    __syncthreads();
+    store = last_ticket != 0;
+    if (store) {
+      // every other part was acknowledged before its ticket was drawn, and all tickets before this one
+      float M = -INFINITY;
+      for (int p = 0; p < sg.n_parts; ++p) {
+        const u64 ml = __hip_atomic_load(reinterpret_cast<const u64*>(part_ml + (int64_t)(sg.first_part + p) * (2 * QT)) + w * 32 + col,
+                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        M = fmaxf(M, __builtin_bit_cast(float, (unsigned)ml));
+      }
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[mb][r] = 0.f;
+      l = 0.f;
+      for (int p = 0; p < sg.n_parts; ++p) {   // in slot order: the sum does not depend on who adds it up
+        const u64 ml = __hip_atomic_load(reinterpret_cast<const u64*>(part_ml + (int64_t)(sg.first_part + p) * (2 * QT)) + w * 32 + col,
+                                         __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float f = __builtin_amdgcn_exp2f(__builtin_bit_cast(float, (unsigned)ml) - M);
+        l = fmaf(f, __builtin_bit_cast(float, (unsigned)(ml >> 32)), l);
+        const u64* po = reinterpret_cast<const u64*>(part_o + (int64_t)(sg.first_part + p) * (QT * D)) + (w * MB * 8) * 64 + lane;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+          for (int h2 = 0; h2 < 8; ++h2) {
+            const u64 v2 = __hip_atomic_load(po + (mb * 8 + h2) * 64, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            o[mb][2 * h2] = fmaf(f, __builtin_bit_cast(float, (unsigned)v2), o[mb][2 * h2]);
+            o[mb][2 * h2 + 1] = fmaf(f, __builtin_bit_cast(float, (unsigned)(v2 >> 32)), o[mb][2 * h2 + 1]);
+          }
+      }
+      if (tid == 0)   // as the next launch expects it
+        __hip_atomic_store(&part_count[sg.counter], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
   const float inv = 1.f / l;
   const int qi = q0 + col;
-  if (qi < N_k) {
+  if (store && qi < N_k) {
     __bf16* orow = out + ((int64_t)d.unit * N_k + qi) * D;
 #pragma unroll
     for (int mb = 0; mb < MB; ++mb) {
@@ -699,6 +794,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
       }
     }
   }
+  if (STREAM && si + 1 < seg_hi) __syncthreads();   // every wave has left the ring before the next segment refills it
+  }  // segments
 }
 
 }  // namespace
@@ -716,8 +813,8 @@ static void launch_mfma_t(hipStream_t s, const UnitDesc* descs, const AttnItem* 
                           float scale, void* out, int kernel) {
   typedef __bf16 T;
   if (kernel != 0)
-    hipLaunchKernelGGL((attn_pipe<D, NW>), dim3(n_items), dim3(64 * NW), 0, s, descs, items,
-                       (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out);
+    hipLaunchKernelGGL((attn_pipe<D, NW, false>), dim3(n_items), dim3(64 * NW), 0, s, descs, items, nullptr, nullptr,
+                       (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out, nullptr, nullptr, nullptr);
   else
     hipLaunchKernelGGL((attn_mfma<D, NW>), dim3(n_items), dim3(64 * NW), 0, s, descs, items,
                        (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out);
@@ -741,6 +838,31 @@ void launch_attn(hipStream_t s, int dtype, int head_dim, const UnitDesc* descs, 
   }
   if (head_dim == 64) launch_mfma_t<64, 4>(s, descs, items, n_items, q, k_cache, v_cache, N_k, scale, out, bf16_kernel);
   else launch_mfma_t<128, 4>(s, descs, items, n_items, q, k_cache, v_cache, N_k, scale, out, bf16_kernel);
+}
+
+// Work-groups of the streamed bf16 kernel that the current device holds at once.
+int attn_stream_slots(int head_dim) {
+  int dev = 0, cus = 0, blocks = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+  const hipError_t e = head_dim == 64
+      ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, attn_pipe<64, 4, true>, 256, 0)
+      : hipOccupancyMaxActiveBlocksPerMultiprocessor(&blocks, attn_pipe<128, 4, true>, 256, 0);
+  if (e != hipSuccess) return 0;
+  return blocks * cus;
+}
+
+void launch_attn_stream(hipStream_t s, int head_dim, const UnitDesc* descs, const AttnSeg* segs, const int32_t* seg_begin,
+                        int n_groups, const void* q, const void* k_cache, const void* v_cache, int N_k, float scale,
+                        void* out, float* part_o, float* part_ml, unsigned* part_count) {
+  if (n_groups <= 0) return;
+  typedef __bf16 T;
+  if (head_dim == 64)
+    hipLaunchKernelGGL((attn_pipe<64, 4, true>), dim3(n_groups), dim3(256), 0, s, descs, nullptr, segs, seg_begin,
+                       (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out, part_o, part_ml, part_count);
+  else
+    hipLaunchKernelGGL((attn_pipe<128, 4, true>), dim3(n_groups), dim3(256), 0, s, descs, nullptr, segs, seg_begin,
+                       (const T*)q, (const T*)k_cache, (const T*)v_cache, N_k, scale, (T*)out, part_o, part_ml, part_count);
 }
 
 }  // namespace hack

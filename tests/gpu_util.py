@@ -59,13 +59,16 @@ def make_hack(cfg_or_none=None, *, heads=None, head_dim=None, dtype=None, max_un
               max_queries=None, n_obs=32, attention=None) -> Hack:
     """attention: None = the library's own choice between its bf16 attention kernels per launch;
     "split" / "tile128" = force the key-split (32-query items) or the 128-query-tile kernel (the
-    deeper software pipeline) for every launch of this context; "tile128_plain" = 128-query tiles
-    through the plain one-block pipeline (the library reads the overrides when the context is created)."""
+    deeper software pipeline, one work item per work-group) for every launch of this context;
+    "stream" = that kernel in its streamed form (the launch cut into equal runs of key blocks) for
+    every launch; "tile128_plain" = 128-query tiles through the plain one-block pipeline (the
+    library reads the overrides when the context is created)."""
     import os
     env = {}
     if attention is not None:
-        env["HACK_ATTN_SPLIT_ITEMS"] = {"split": "2000000000", "tile128": "0", "tile128_plain": "0"}[attention]
+        env["HACK_ATTN_SPLIT_ITEMS"] = {"split": "2000000000", "tile128": "0", "tile128_plain": "0", "stream": "0"}[attention]
         env["HACK_ATTN_PIPE"] = "0" if attention == "tile128_plain" else "1"
+        env["HACK_ATTN_STREAM"] = "1" if attention == "stream" else "0"
     saved = {k: os.environ.get(k) for k in env}
     os.environ.update(env)
     try:

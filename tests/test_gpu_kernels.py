@@ -330,6 +330,11 @@ def test_score_cache_only_custom_rows_and_inactive_units():
     ("bf16", 128, 130, [96, 97, 192, 193, 224, 225, 256, 289], 2e-2, "tile128"),      # 3 .. 10 key blocks: every
     ("bf16", 64, 130, [96, 97, 192, 193, 224, 225, 256, 289], 2e-2, "tile128"),       # way in and out of the steady loop
     ("bf16", 128, 130, [320, 321, 351, 352, 353, 384, 416, 449], 2e-2, "tile128"),
+    ("bf16", 128, 300, [1, 2, 63, 64, 65, 1943, 127, 700], 2e-2, "stream"),           # work items cut into segments,
+    ("bf16", 64, 100, [102, 306, 1, 33, 562, 91, 128, 129], 2e-2, "stream"),          # partial results added up by the
+    ("bf16", 128, 130, [96, 97, 192, 193, 224, 225, 256, 289], 2e-2, "stream"),       # work-group that finishes last
+    ("bf16", 64, 130, [320, 321, 351, 352, 353, 384, 416, 449], 2e-2, "stream"),
+    ("bf16", 128, 1, [1, 5, 21, 57, 121, 265, 64, 32], 2e-2, "stream"),
     ("f32", 64, 100, [102, 306, 1, 33, 562, 91, 128, 129], 1e-4, None),
     ("f32", 128, 70, [1, 2, 63, 64, 65, 300, 127, 31], 1e-4, None),
 ])
@@ -349,16 +354,19 @@ def test_attention_matches_oracle(dtype, d, Nk, lens, tol, kernel):
         rows = [(wl.bf16_to_f32(wl.bf16_round(k)), v) for k, v in rows]
     cache, _ = u.build_cache(rows, d, dtype, pad_rows=1, fill=50.0)
     q = u.rand_values(rng, (B, H, Nk, d), dtype)
-    out = torch.full((B, H, Nk, d), 7.0, dtype=hk.torch_dtype, device=u.DEV)
-    hk.attn(u.to_dev(q, dtype), cache, scale, out)
-    torch.cuda.synchronize()
-    got = u.from_dev(out)
-    for uu in range(U):
-        b, h = divmod(uu, H)
-        want = ho.attention(q[b, h].astype(np.float64), rows[uu][0].astype(np.float64),
-                            rows[uu][1].astype(np.float64), scale)
-        err = np.abs(got[b, h] - want).max()
-        assert err < tol, (uu, lens[uu], err)
+    # twice with different queries: the second launch reuses whatever scratch the first one left
+    for rep in range(2):
+        out = torch.full((B, H, Nk, d), 7.0, dtype=hk.torch_dtype, device=u.DEV)
+        hk.attn(u.to_dev(q, dtype), cache, scale, out)
+        torch.cuda.synchronize()
+        got = u.from_dev(out)
+        for uu in range(U):
+            b, h = divmod(uu, H)
+            want = ho.attention(q[b, h].astype(np.float64), rows[uu][0].astype(np.float64),
+                                rows[uu][1].astype(np.float64), scale)
+            err = np.abs(got[b, h] - want).max()
+            assert err < tol, (rep, uu, lens[uu], err)
+        q = u.rand_values(rng, (B, H, Nk, d), dtype)
     hk.close()
 
 

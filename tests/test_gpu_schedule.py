@@ -207,13 +207,14 @@ def test_swapped_policies_and_single_class_masks():
         assert stats["mismatch"] == 0 and stats["compress_events"] > 0
 
 
-@pytest.mark.parametrize("attention", ["split", "tile128", "tile128_plain"])
+@pytest.mark.parametrize("attention", ["split", "tile128", "tile128_plain", "stream"])
 def test_schedule_with_either_attention_kernel_forced(attention):
     """hack_step picks the attention kernel per step (key-split with the append fused
     into it for steps with few queries, 128-query tiles after a separate append
     otherwise).  Forcing one kernel for every step covers the combinations the
     default choice does not reach at these sizes: the key-split kernel after a
-    gather and on long caches, the tiled kernel on the smallest steps.  Outputs,
+    gather and on long caches, the tiled kernel on the smallest steps, the tiled
+    kernel's streamed form (work items cut into segments) on short caches.  Outputs,
     kept sets, positions and the final cache contents are checked as usual."""
     cfg = wl.get_config(1, batch=1)
     stats = run_free(cfg, 0, list(range(0, cfg.n_units, 4)), attention=attention)
@@ -369,7 +370,7 @@ def test_step_capacity_and_argument_errors():
     hk.close()
 
 
-@pytest.mark.parametrize("cfg_id,batch,attention", [(1, 2, None), (1, 2, "tile128"), (2, None, None)])
+@pytest.mark.parametrize("cfg_id,batch,attention", [(1, 2, None), (1, 2, "tile128"), (1, 2, "stream"), (2, None, None)])
 def test_graph_replays_reproduce_the_eager_schedule(cfg_id, batch, attention):
     """The whole schedule captured in a HIP graph (as bench.py launches it) is
     replayed several times, with eager work and synchronisations in between;
