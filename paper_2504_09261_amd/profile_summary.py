@@ -24,7 +24,22 @@ import sys
 csv.field_size_limit(1 << 30)
 
 
+def _own_mangled(name: str) -> str:
+    """The profiler leaves very long names mangled: kernel<int/bool template arguments> of this library's own kernels."""
+    m = re.match(r"_ZN4hack\d+_GLOBAL__N_1(\d+)", name)
+    if not m:
+        return name
+    n = int(m.group(1))
+    base, rest = name[m.end():m.end() + n], name[m.end() + n:]
+    args = []
+    if rest.startswith("I"):
+        for a in re.finditer(r"L([ib])(\d+)E", rest[1:rest.index("EEE") + 1] if "EEE" in rest else rest):
+            args.append(a.group(2) if a.group(1) == "i" else ("true" if a.group(2) == "1" else "false"))
+    return base + ("<" + ",".join(args) + ">" if args else "")
+
+
 def short(name: str) -> str:
+    name = _own_mangled(name)
     name = re.sub(r"\(anonymous namespace\)::|hack::|void ", "", name)
     name = re.sub(r"\(.*$", "", name)
     return name[:72]
