@@ -271,11 +271,11 @@ void build_attn_items(const std::vector<UnitDesc>& descs, int N_k, int tile_rows
     int x = 0;
     for (int i = 1; i < X; ++i) if (load[i] < load[x]) x = i;   // least-loaded XCD
     load[x] += (int64_t)descs[order[r]].n_out * tiles;
-    for (int t = 0; t < tiles; ++t) per[x].push_back(AttnItem{order[r], t});
+    for (int t = 0; t < tiles; ++t) per[x].push_back(make_attn_item(descs[order[r]], order[r], t));
   }
   size_t longest = 0;
   for (int x = 0; x < X; ++x) longest = std::max(longest, per[x].size());
-  items->assign(longest * X, AttnItem{-1, 0});
+  items->assign(longest * X, attn_item_padding());
   for (int x = 0; x < X; ++x)
     for (size_t i = 0; i < per[x].size(); ++i) (*items)[i * X + x] = per[x][i];
 }

@@ -31,11 +31,27 @@ static_assert(sizeof(UnitDesc) == 64, "UnitDesc must stay 64 bytes");
 
 enum : int32_t { MOVE_NONE = 0, MOVE_APPEND = 1, MOVE_GATHER = 2 };
 
-// One attention work item: a tile of queries of one unit.
-struct AttnItem {
-  int32_t desc;    // index into the UnitDesc table
-  int32_t q_tile;  // first query row = q_tile * (rows per tile)
+// One attention work item: a tile of queries of one unit.  It carries copies of the descriptor
+// fields the attention kernels read, so that a work-group has one dependent table load in front of
+// its first K/V copy instead of two (the small scale steps are pure latency chains).
+struct alignas(16) AttnItem {
+  int32_t desc;     // index into the UnitDesc table; < 0: padding entry, nothing to do
+  int32_t q_tile;   // first query row = q_tile * (rows per tile)
+  int32_t unit;     // UnitDesc::unit
+  int32_t n_out;    // UnitDesc::n_out
+  int64_t out_off;  // UnitDesc::out_off
+  int64_t in_off;   // UnitDesc::in_off
+  int32_t len_in;   // UnitDesc::len_in
+  int32_t pad[3];
 };
+static_assert(sizeof(AttnItem) == 48, "AttnItem must stay 48 bytes");
+inline AttnItem make_attn_item(const UnitDesc& d, int desc, int q_tile) {
+  AttnItem it{};
+  it.desc = desc; it.q_tile = q_tile; it.unit = d.unit; it.n_out = d.n_out; it.out_off = d.out_off; it.in_off = d.in_off;
+  it.len_in = d.len_in;
+  return it;
+}
+inline AttnItem attn_item_padding() { AttnItem it{}; it.desc = -1; return it; }
 
 struct CachePtrs {
   void* k;

@@ -50,7 +50,7 @@ __global__ __launch_bounds__(kGenQ) void attn_generic(
     T* __restrict__ out) {
   const AttnItem it = items[blockIdx.x];
   if (it.desc < 0) return;
-  const UnitDesc d = descs[it.desc];
+  const AttnItem& d = it;   // the item carries the descriptor fields read here
   const int len = d.n_out;
   const int qi = it.q_tile * kGenQ + threadIdx.x;
   const bool qvalid = qi < N_k;
@@ -140,7 +140,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_mfma(
 
   const AttnItem it = items[blockIdx.x];
   if (it.desc < 0) return;
-  const UnitDesc d = descs[it.desc];
+  const AttnItem& d = it;   // the item carries the descriptor fields read here
   const int len = d.n_out;
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -477,14 +477,16 @@ __global__ __launch_bounds__(64 * NW, 2) void attn_pipe(
   if (STREAM) asm volatile("" : "+v"(lane));
   const int col = lane & 31, half = lane >> 5;
   AttnSeg sg;
+  AttnItem d;      // unit, n_out, out_off of the work item
   if (STREAM) {
     sg = segs[si];
+    const UnitDesc ud = descs[sg.desc];
+    d.unit = ud.unit; d.n_out = ud.n_out; d.out_off = ud.out_off;
   } else {
-    const AttnItem it = items[si];
-    if (it.desc < 0) return;
-    sg = AttnSeg{it.desc, it.q_tile, 0, 0x3fffffff, -1, 0, 0, 0};
+    d = items[si];
+    if (d.desc < 0) return;
+    sg = AttnSeg{d.desc, d.q_tile, 0, 0x3fffffff, -1, 0, 0, 0};
   }
-  const UnitDesc d = descs[sg.desc];
   const int key0 = sg.blk0 * kKB;                                               // first key of the segment
   const int len = (int)min((int64_t)sg.blk1 * kKB, (int64_t)d.n_out) - key0;    // its keys
 

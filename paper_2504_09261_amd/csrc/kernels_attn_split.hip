@@ -51,7 +51,7 @@ __global__ __launch_bounds__(64 * kWaves, 2) void attn_split(
 
   const AttnItem it = items[blockIdx.x];
   if (it.desc < 0) return;
-  const UnitDesc d = descs[it.desc];
+  const AttnItem& d = it;   // the item carries the descriptor fields read here
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;
