@@ -140,4 +140,154 @@ inline void plan_attn_stream(const int32_t* n_keys, int n_desc, int tiles, int s
   }
 }
 
+// ---- cutting single work items of a launch that fits the device at once ------------------------
+// When a launch has no more work items than the device holds work-groups, every item starts at once
+// and the launch lasts as long as its slowest compute unit.  Two work-groups share a compute unit,
+// and work-groups are placed one per compute unit first, then a second one each, in launch order
+// within an XCD (work-group id % 8); the one that arrived first is served first.  With `solo`,
+// `older` and `younger` the time per 32-key block of a work-group alone, of the first and of the
+// second of a pair, a compute unit that holds a pieces-long older and a b-long younger work-group
+// finishes at pair_time(a, b).  The planner lays an XCD's pieces out so that the largest second
+// occupants meet the smallest first occupants, and cuts pieces of the slowest compute unit in two
+// while that shortens the modelled launch (each cut costs a pipeline fill, a partial result and its
+// share of adding the parts up: ovh_part against ovh_whole, in blocks).
+struct AttnPairModel {
+  double solo, older, younger;     // us per key block
+  double ovh_whole, ovh_part;      // fixed cost of a whole work item / of a piece of a cut one, in key blocks
+};
+
+inline double attn_pair_time(double a, double b, const AttnPairModel& m) {
+  if (b <= 0) return m.solo * a;
+  const double t_old = m.older * a, t_young = m.younger * b;
+  if (t_young <= t_old) return t_young + m.solo * (a - t_young / m.older);   // the younger one ends first
+  return t_old + m.solo * (b - t_old / m.younger);
+}
+
+struct AttnLaneItem {
+  int32_t desc, q_tile, n_blocks;
+};
+
+namespace attn_plan_detail {
+struct Piece {
+  int item, b0, b1;
+  bool cut;
+};
+inline double eff(const Piece& p, const AttnPairModel& m) { return (p.b1 - p.b0) + (p.cut ? m.ovh_part : m.ovh_whole); }
+// Sorts the pieces by decreasing size and returns the modelled time of the lane and, in *crit, the piece
+// to cut next (the second occupant of the slowest compute unit if it can be cut, else the first; -1: none).
+inline double lane_time(std::vector<Piece>* L, int cus, int min_blocks, const AttnPairModel& m, int* crit) {
+  std::stable_sort(L->begin(), L->end(), [&](const Piece& a, const Piece& b) { return eff(a, m) > eff(b, m); });
+  const int n = (int)L->size(), first = std::min(n, cus);
+  double worst = -1.0;
+  int wa = -1, wb = -1;
+  for (int j = 0; j < first; ++j) {           // j-th smallest first occupant, j-th largest second occupant
+    const int ia = first - 1 - j, ib = cus + j;
+    const double t = attn_pair_time(eff((*L)[ia], m), ib < n ? eff((*L)[ib], m) : 0.0, m);
+    if (t > worst) { worst = t; wa = ia; wb = ib < n ? ib : -1; }
+  }
+  auto cuttable = [&](int i) { return i >= 0 && (*L)[i].b1 - (*L)[i].b0 >= 2 * min_blocks; };
+  *crit = cuttable(wb) ? wb : (cuttable(wa) ? wa : -1);
+  return worst;
+}
+}  // namespace attn_plan_detail
+
+// lanes[x]: the work items of XCD x (work-group id % 8 == x) in any order.  Fills *plan (one segment per
+// work-group, in the launch order described above) and returns true if cutting shortens the modelled launch
+// by at least min_gain (a fraction); *before / *after get the modelled times in us.  Returns false, leaving
+// *plan unspecified, when the launch does not fit the device at once or nothing is gained.
+inline bool plan_attn_cuts(const std::vector<AttnLaneItem> (&lanes)[kAttnXcds], int cus_per_xcd, int min_blocks,
+                           const AttnPairModel& m, double min_gain, AttnStreamPlan* plan, double* before, double* after) {
+  using attn_plan_detail::Piece;
+  *before = *after = 0.0;
+  if (cus_per_xcd <= 0) return false;
+  min_blocks = std::max(1, min_blocks);
+  for (int x = 0; x < kAttnXcds; ++x)
+    if ((int)lanes[x].size() > 2 * cus_per_xcd) return false;
+  std::vector<std::vector<Piece>> states[kAttnXcds];   // lane state after k cuts
+  std::vector<double> times[kAttnXcds];
+  double t0 = 0.0, t_best = 0.0;
+  for (int x = 0; x < kAttnXcds; ++x) {
+    std::vector<Piece> L;
+    for (int i = 0; i < (int)lanes[x].size(); ++i) L.push_back(Piece{i, 0, lanes[x][i].n_blocks, false});
+    if (L.empty()) {
+      states[x].push_back(L);
+      times[x].push_back(0.0);
+      continue;
+    }
+    for (;;) {
+      int crit = -1;
+      const double t = attn_plan_detail::lane_time(&L, cus_per_xcd, min_blocks, m, &crit);
+      states[x].push_back(L);
+      times[x].push_back(t);
+      if (crit < 0 || (int)L.size() >= 2 * cus_per_xcd) break;
+      // all pieces of the item become pieces of a cut item
+      const Piece p = L[crit];
+      const int mid = p.b0 + (p.b1 - p.b0) / 2;
+      for (Piece& q : L) if (q.item == p.item) q.cut = true;
+      L[crit] = Piece{p.item, p.b0, mid, true};
+      L.push_back(Piece{p.item, mid, p.b1, true});
+    }
+    t0 = std::max(t0, times[x][0]);
+    t_best = std::max(t_best, *std::min_element(times[x].begin(), times[x].end()));
+  }
+  *before = t0;
+  *after = t_best;
+  if (!(t_best <= (1.0 - min_gain) * t0) || t_best >= t0) return false;
+  // per lane the fewest cuts that reach the launch's best time
+  plan->segs.clear();
+  plan->n_parts = plan->n_counters = 0;
+  std::vector<AttnSeg> out[kAttnXcds];
+  bool any_cut = false;
+  for (int x = 0; x < kAttnXcds; ++x) {
+    size_t k = 0;
+    while (times[x][k] > t_best) ++k;
+    std::vector<Piece> L = states[x][k];   // sorted by decreasing size
+    any_cut = any_cut || k > 0;
+    // parts of the cut items, numbered by position inside the item
+    const int n_items = (int)lanes[x].size();
+    std::vector<std::vector<int>> of_item(n_items);
+    for (int i = 0; i < (int)L.size(); ++i) of_item[L[i].item].push_back(i);
+    std::vector<AttnSeg> seg(L.size());
+    for (int it = 0; it < n_items; ++it) {
+      std::vector<int>& v = of_item[it];
+      std::sort(v.begin(), v.end(), [&](int a, int b) { return L[a].b0 < L[b].b0; });
+      for (size_t j = 0; j < v.size(); ++j) {
+        AttnSeg s{};
+        s.desc = lanes[x][it].desc;
+        s.q_tile = lanes[x][it].q_tile;
+        s.blk0 = L[v[j]].b0;
+        s.blk1 = L[v[j]].b1;
+        if (v.size() > 1) {
+          s.part = plan->n_parts + (int)j;
+          s.first_part = plan->n_parts;
+          s.n_parts = (int)v.size();
+          s.counter = plan->n_counters;
+        } else {
+          s.part = -1;
+        }
+        seg[v[j]] = s;
+      }
+      if (v.size() > 1) {
+        plan->n_parts += (int)v.size();
+        plan->n_counters += 1;
+      }
+    }
+    // launch order: first occupants smallest first, then second occupants largest first
+    const int first = std::min((int)L.size(), cus_per_xcd);
+    for (int j = 0; j < first; ++j) out[x].push_back(seg[first - 1 - j]);
+    for (int j = first; j < (int)L.size(); ++j) out[x].push_back(seg[j]);
+  }
+  if (!any_cut) return false;
+  size_t longest = 0;
+  for (int x = 0; x < kAttnXcds; ++x) longest = std::max(longest, out[x].size());
+  plan->seg_begin.assign(1, 0);
+  for (size_t r = 0; r < longest; ++r)
+    for (int x = 0; x < kAttnXcds; ++x) {
+      if (r < out[x].size()) plan->segs.push_back(out[x][r]);
+      plan->seg_begin.push_back((int32_t)plan->segs.size());
+    }
+  plan->n_groups = (int)longest * kAttnXcds;
+  return true;
+}
+
 }  // namespace hack

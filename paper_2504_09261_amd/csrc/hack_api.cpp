@@ -83,7 +83,8 @@ struct hack_ctx {
   int split_max_items = 0;       // launches with at most this many 32-query attention items use the key-split kernel
   int attn_kernel = 1;           // bf16 kernel of the 128-query items: 1 = deeper pipeline, 0 = plain (HACK_ATTN_PIPE=0)
   // streamed form of that kernel: the launch is cut into equal runs of key blocks, one per resident work-group
-  int attn_stream = 0;           // 0: off (default, see use_stream_attention), 1: every launch of the 128-query kernel, 2: A/B aid (HACK_ATTN_STREAM)
+  int attn_stream = -1;          // HACK_ATTN_STREAM; -1 (default): cut single work items where the pair model gains, 0: never, 1: equal runs
+                                 // for every launch of the 128-query kernel, 2: A/B aid, 4: every cut the model likes (see use_stream_attention)
   int attn_slots = 0;            // work-groups of the streamed kernel the device holds at once
   float* part_o = nullptr;       // [2 * attn_slots, 128, head_dim] unnormalised partial outputs
   float* part_ml = nullptr;      // [2 * attn_slots, 2, 128] their references and normalisers
@@ -310,10 +311,22 @@ bool use_split_attention(const hack_ctx* ctx, int n_units, int N_k) {
 // partial result written and 3-4 us per part added up.
 // `shared` says that another attention launch of the context may run at the same time (the partial-result
 // arrays are the context's), which rules the streamed form out.
+// What the library does by default (HACK_ATTN_STREAM unset) is narrower: launches whose work items all start
+// at once (no more items than resident work-groups) keep whole work items, and plan_attn_cuts halves the few
+// whose compute unit would finish last under the measured pair model, if that shortens the modelled launch by
+// kCutMinGain.  On the 1024^2 benchmark workloads this fires at scale step 11 with 16 heads x batch 2 (416 work
+// items on 256 compute units: the long items that would share a compute unit with another long one are
+// halved; 113.7 -> 98.8 us measured, 111.8 -> 89.3 modelled) and at step 9 with 32 heads x batch 2 (50.3 ->
+// 42.8 us measured, 45.3 -> 35.0 modelled); launches with more work items than resident work-groups are
+// left alone (there the model is 10-15 % off).  HACK_ATTN_STREAM=0 switches it off, =4 applies every cut
+// the model likes (tests).
+constexpr AttnPairModel kPairModel128{0.55, 0.75, 1.0, 4.0, 14.0};   // us per key block alone / first / second of a pair; fixed costs in blocks
+constexpr double kCutMinGain = 0.05;
+constexpr int kCutMinBlocks = 8;
 constexpr int kStreamOverheadBlocks = 4;   // start and end of a segment, in key blocks of the steady loop
 constexpr int kStreamMinBlocks = 4;        // shortest segment a work item is cut into
 bool use_stream_attention(const hack_ctx* ctx, const std::vector<UnitDesc>& descs, int N_k, bool shared, AttnStreamPlan* plan) {
-  if (ctx->cfg.dtype != HACK_BF16 || ctx->attn_kernel == 0 || ctx->attn_stream <= 0 || ctx->attn_slots <= 0 || shared) return false;
+  if (ctx->cfg.dtype != HACK_BF16 || ctx->attn_kernel == 0 || ctx->attn_stream == 0 || ctx->attn_slots <= 0 || shared) return false;
   if (descs.empty()) return false;
   const int tile = attn_q_tile_rows(ctx->cfg.dtype, ctx->cfg.head_dim, (int)descs.size(), N_k);
   if (tile != 128) return false;
@@ -332,6 +345,23 @@ bool use_stream_attention(const hack_ctx* ctx, const std::vector<UnitDesc>& desc
     plan->n_groups = (int)items.size();
     plan->n_parts = plan->n_counters = 0;
     return plan->n_groups > 0;
+  }
+  if (ctx->attn_stream < 0 || ctx->attn_stream == 4) {
+    // whole work items, a few of them cut in two where the pair model says the launch gets shorter (plan_attn_cuts)
+    int cus = 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, ctx->cfg.device) != hipSuccess || cus < kAttnXcds) return false;
+    const bool forced = ctx->attn_stream == 4;
+    // the model's constants were measured for head_dim 128, two work-groups per compute unit
+    if (!forced && (ctx->cfg.head_dim != 128 || ctx->attn_slots != 2 * cus)) return false;
+    std::vector<AttnItem> items;
+    build_attn_items(descs, N_k, tile, &items);
+    std::vector<AttnLaneItem> lanes[kAttnXcds];
+    for (size_t i = 0; i < items.size(); ++i)
+      if (items[i].desc >= 0)
+        lanes[i % kAttnXcds].push_back(AttnLaneItem{items[i].desc, items[i].q_tile, (items[i].n_out + kAttnKeyBlock - 1) / kAttnKeyBlock});
+    double before = 0.0, after = 0.0;
+    if (!plan_attn_cuts(lanes, cus / kAttnXcds, kCutMinBlocks, kPairModel128, forced ? 1e-9 : kCutMinGain, plan, &before, &after)) return false;
+    return plan->n_groups > 0 && plan->n_parts <= 2 * ctx->attn_slots && plan->n_counters <= ctx->attn_slots;
   }
   plan_attn_stream(n_keys.data(), (int)descs.size(), (N_k + tile - 1) / tile, ctx->attn_slots, kStreamOverheadBlocks,
                    kStreamMinBlocks, plan);

@@ -61,14 +61,15 @@ def make_hack(cfg_or_none=None, *, heads=None, head_dim=None, dtype=None, max_un
     "split" / "tile128" = force the key-split (32-query items) or the 128-query-tile kernel (the
     deeper software pipeline, one work item per work-group) for every launch of this context;
     "stream" = that kernel in its streamed form (the launch cut into equal runs of key blocks) for
-    every launch; "tile128_plain" = 128-query tiles through the plain one-block pipeline (the
+    every launch; "cut" = that kernel with every single work item cut in two that the library's
+    pair model likes, however small the gain; "tile128_plain" = 128-query tiles through the plain one-block pipeline (the
     library reads the overrides when the context is created)."""
     import os
     env = {}
     if attention is not None:
-        env["HACK_ATTN_SPLIT_ITEMS"] = {"split": "2000000000", "tile128": "0", "tile128_plain": "0", "stream": "0"}[attention]
+        env["HACK_ATTN_SPLIT_ITEMS"] = {"split": "2000000000", "tile128": "0", "tile128_plain": "0", "stream": "0", "cut": "0"}[attention]
         env["HACK_ATTN_PIPE"] = "0" if attention == "tile128_plain" else "1"
-        env["HACK_ATTN_STREAM"] = "1" if attention == "stream" else "0"
+        env["HACK_ATTN_STREAM"] = {"stream": "1", "cut": "4"}.get(attention, "0")
     saved = {k: os.environ.get(k) for k in env}
     os.environ.update(env)
     try:

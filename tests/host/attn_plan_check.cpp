@@ -3,6 +3,7 @@
 // the work-groups get equal work.  No GPU involved.
 #include <cstdio>
 #include <cstdlib>
+#include <cmath>
 #include <map>
 #include <random>
 #include <vector>
@@ -78,7 +79,94 @@ static void check_plan(const std::vector<int32_t>& n_keys, int tiles, int slots,
   }
 }
 
+// plan_attn_cuts: validity of the plan (every block once, parts numbered consistently, one segment per
+// work-group, lanes kept apart) and what the model promises.
+static bool check_cuts(const std::vector<int32_t>& n_keys, int tiles, int cus_per_xcd, double min_gain, double* gain) {
+  const AttnPairModel m{0.55, 0.75, 1.0, 4.0, 14.0};
+  // lanes as the library deals them: units by decreasing length to the least loaded XCD, tiles adjacent
+  std::vector<int> order(n_keys.size());
+  for (size_t i = 0; i < order.size(); ++i) order[i] = (int)i;
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return n_keys[a] > n_keys[b]; });
+  std::vector<AttnLaneItem> lanes[kAttnXcds];
+  long load[kAttnXcds] = {0};
+  for (int u : order) {
+    int x = 0;
+    for (int i = 1; i < kAttnXcds; ++i) if (load[i] < load[x]) x = i;
+    load[x] += (long)n_keys[u] * tiles;
+    for (int t = 0; t < tiles; ++t) lanes[x].push_back(AttnLaneItem{u, t, (n_keys[u] + 31) / 32});
+  }
+  AttnStreamPlan p;
+  double before = 0, after = 0;
+  const bool ok = plan_attn_cuts(lanes, cus_per_xcd, 8, m, min_gain, &p, &before, &after);
+  *gain = before > 0 ? 1.0 - after / before : 0.0;
+  if (!ok) return false;
+  CHECK(after < before && after <= (1.0 - min_gain) * before);
+  CHECK(p.n_groups % kAttnXcds == 0 && (int)p.seg_begin.size() == p.n_groups + 1);
+  CHECK(p.n_groups <= 2 * cus_per_xcd * kAttnXcds);                      // still a single round
+  CHECK(p.n_counters > 0 && p.n_parts >= 2 * p.n_counters);
+  std::map<std::pair<int, int>, std::vector<AttnSeg>> by_item;
+  for (int g = 0; g < p.n_groups; ++g) {
+    CHECK(p.seg_begin[g + 1] - p.seg_begin[g] <= 1);                      // one segment per work-group
+    for (int a = p.seg_begin[g]; a < p.seg_begin[g + 1]; ++a) {
+      const AttnSeg& s = p.segs[a];
+      by_item[{s.desc, s.q_tile}].push_back(s);
+      // an item stays on the XCD the library dealt it to
+      bool found = false;
+      for (const AttnLaneItem& li : lanes[g % kAttnXcds]) found = found || (li.desc == s.desc && li.q_tile == s.q_tile);
+      CHECK(found);
+    }
+  }
+  CHECK(by_item.size() == n_keys.size() * (size_t)tiles);
+  std::vector<int> part_used(p.n_parts, 0);
+  for (auto& kv : by_item) {
+    std::vector<AttnSeg> v = kv.second;
+    std::sort(v.begin(), v.end(), [](const AttnSeg& a, const AttnSeg& b) { return a.blk0 < b.blk0; });
+    const int nb = (n_keys[kv.first.first] + 31) / 32;
+    int at = 0;
+    for (size_t i = 0; i < v.size(); ++i) {
+      CHECK(v[i].blk0 == at && v[i].blk1 > v[i].blk0);
+      at = v[i].blk1;
+      if (v.size() == 1) { CHECK(v[i].part < 0); continue; }
+      CHECK(v[i].blk1 - v[i].blk0 >= 8);
+      CHECK(v[i].n_parts == (int)v.size() && v[i].first_part == v[0].first_part && v[i].counter == v[0].counter);
+      CHECK(v[i].part == v[i].first_part + (int)i && v[i].part < p.n_parts);
+      if (v[i].part >= 0 && v[i].part < p.n_parts) ++part_used[v[i].part];
+    }
+    CHECK(at == nb || (v.size() == 1 && v[0].blk1 >= nb));
+  }
+  for (int u : part_used) CHECK(u == 1);
+  return true;
+}
+
 int main() {
+  {
+    const AttnPairModel m{0.55, 0.75, 1.0, 4.0, 14.0};
+    // alone; the second one ends first; the first one ends first
+    CHECK(std::fabs(attn_pair_time(100, 0, m) - 55.0) < 1e-9);
+    CHECK(std::fabs(attn_pair_time(120, 60, m) - (60.0 + 0.55 * (120 - 80))) < 1e-9);
+    CHECK(std::fabs(attn_pair_time(100, 100, m) - (75.0 + 0.55 * 25)) < 1e-9);
+    double gain = 0;
+    // scale step 11 of the benchmark workload: 20 units of 3885 keys, 12 of 1943, 13 query tiles: more long
+    // items than compute units, so some compute units hold two of them until those are halved
+    std::vector<int32_t> n;
+    for (int u = 0; u < 32; ++u) n.push_back(u % 16 < 6 ? 1943 : 3885);
+    CHECK(check_cuts(n, 13, 32, 0.05, &gain) && gain > 0.1);
+    // the last scale step (32 tiles: 1024 items) does not fit the device at once: left alone
+    CHECK(!check_cuts(n, 32, 32, 0.05, &gain));
+    // one work item per compute unit at most and equal lengths: nothing to gain from halving all of them
+    std::vector<int32_t> eq(32, 1497);
+    CHECK(!check_cuts(eq, 8, 32, 0.05, &gain));
+    std::mt19937 rng(777);
+    int fired = 0;
+    for (int rep = 0; rep < 200; ++rep) {
+      const int n_desc = 1 + rng() % 48, tiles = 1 + rng() % 6, cus = 1 + rng() % 32;
+      std::vector<int32_t> v(n_desc);
+      for (int& x : v) x = 1 + rng() % 8000;
+      fired += check_cuts(v, tiles, cus, rep % 2 ? 0.05 : 1e-9, &gain) ? 1 : 0;
+    }
+    CHECK(fired > 20);
+  }
+
   // the benchmark workload's large steps: 12 units of 1943 keys, 20 of 3885 (2521 at the first), tiles 5 .. 32
   for (int tiles : {5, 8, 13, 18, 32}) {
     std::vector<int32_t> n;

@@ -335,6 +335,9 @@ def test_score_cache_only_custom_rows_and_inactive_units():
     ("bf16", 128, 130, [96, 97, 192, 193, 224, 225, 256, 289], 2e-2, "stream"),       # work-group that finishes last
     ("bf16", 64, 130, [320, 321, 351, 352, 353, 384, 416, 449], 2e-2, "stream"),
     ("bf16", 128, 1, [1, 5, 21, 57, 121, 265, 64, 32], 2e-2, "stream"),
+    ("bf16", 128, 300, [1, 2, 63, 64, 65, 1943, 127, 700], 2e-2, "cut"),              # whole work items, the longest halved
+    ("bf16", 64, 100, [102, 306, 1, 33, 562, 91, 128, 129], 2e-2, "cut"),
+    ("bf16", 128, 130, [320, 321, 351, 352, 1353, 384, 416, 2047], 2e-2, "cut"),
     ("f32", 64, 100, [102, 306, 1, 33, 562, 91, 128, 129], 1e-4, None),
     ("f32", 128, 70, [1, 2, 63, 64, 65, 300, 127, 31], 1e-4, None),
 ])

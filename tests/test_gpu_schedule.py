@@ -207,7 +207,7 @@ def test_swapped_policies_and_single_class_masks():
         assert stats["mismatch"] == 0 and stats["compress_events"] > 0
 
 
-@pytest.mark.parametrize("attention", ["split", "tile128", "tile128_plain", "stream"])
+@pytest.mark.parametrize("attention", ["split", "tile128", "tile128_plain", "stream", "cut"])
 def test_schedule_with_either_attention_kernel_forced(attention):
     """hack_step picks the attention kernel per step (key-split with the append fused
     into it for steps with few queries, 128-query tiles after a separate append
