@@ -327,10 +327,10 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
 
   // ---- A: logits of the item's tiles ---------------------------------------
   // Between A and C a logit waits in registers either as its fixed-point value (one register; 2^t is
-  // formed again in C) or, for the small items (TILES <= 2, where the registers are there), as the
+  // formed again in C) or, for all but the largest items (TILES <= 4, where the registers are there), as the
   // double 2^t of that same fixed-point value (two registers; nothing is recomputed).  Both forms give
   // the same numbers bit for bit.
-  constexpr bool kParkP = TILES <= 2;
+  constexpr bool kParkP = TILES <= 4;
   int tq[kParkP ? 1 : kItemTiles][16];
   double pq[kParkP ? kItemTiles : 1][16];
   auto p_of = [&](int t, int r) -> double { return kParkP ? pq[t][r] : exp2_fix(tq[t][r]); };
