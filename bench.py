@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--head-variance", action="store_true",
                     help="also time the offline head-classification kernels (attention variance of every unit at the "
                          "final step over the full cache) and report them in a head_variance object")
+    ap.add_argument("--final-merge", action="store_true",
+                    help="also time the schedule with the final-step merge of the contextual units in its last step")
     ap.add_argument("--no-full-cache-reference", action="store_true",
                     help="skip the extra run of the same schedule without compression (full_cache_reference)")
     ap.add_argument("--full-budget", action="store_true",
@@ -78,12 +80,14 @@ class LayerState:
                 dst.append(t.contiguous())
             self.o.append(torch.empty_like(self.q[-1]))
         self.host = data
+        self.final_merge = False   # the last step with the final-step merge of the contextual units
 
     def run(self, hk):
         c = self.cfg
         self.mc.reset()
         for i in range(c.n_steps):
-            hk.step(self.mc, self.q[i], self.k[i], self.v[i], self.types, self.budgets[i], c.n_init, c.scale, self.o[i])
+            hk.step(self.mc, self.q[i], self.k[i], self.v[i], self.types, self.budgets[i], c.n_init, c.scale, self.o[i],
+                    final=self.final_merge and i == c.n_steps - 1)
 
 
 def plan_of(cfg, budgets):
@@ -415,8 +419,8 @@ def main():
         n_attn = len(bd["attn"])
         tf = tot["attn_flop"] / (attn_ms * 1e-3) / 1e12
         if cfg.dtype == "bf16":
-            # The dominant kernel is attn_mfma (128-query work items); the early steps with few
-            # queries run the key-split kernel attn_split.  The roofline entry is attn_mfma's own:
+            # The dominant kernel is attn_pipe (128-query work items); the early steps with few
+            # queries run the key-split kernel attn_split.  The roofline entry is attn_pipe's own:
             # flop of the steps it serves / its launch time; every step together is listed beside it.
             own = [i for i in range(n_attn) if hk.attn_variant(cfg.batch, cfg.N[i]) == 0]
             own_flop = sum(work[i]["attn_flop"] for i in own)
@@ -458,6 +462,23 @@ def main():
 
     if args.head_variance and cfg.dtype == "bf16":
         result["head_variance"] = head_variance_leg(hk, layers[0], torch)
+
+    if args.final_merge and cfg.dtype == "bf16" and not args.full_budget:
+        # the same schedule with the last step through hack_step_final (outside `value`: the merge belongs to the
+        # last generation step of an image only)
+        for ls in layers:
+            ls.final_merge = True
+        for ls in layers:
+            ls.run(hk)   # uploads the launch tables of the merging step
+        torch.cuda.synchronize()
+        ms_merge = time_schedule(layers, args.steps, args.warmup)
+        for ls in layers:
+            ls.final_merge = False
+        last = plan_of(cfg, layers[0].budgets)[-1]
+        merging = [u for u in range(cfg.n_units) if layers[0].types[u % cfg.heads] == 0 and last[2][u] < last[1][u]]
+        flop = sum(2.0 * float(last[1][u]) * float(last[2][u]) * cfg.head_dim for u in merging)
+        result["final_merge"] = {"us_per_layer": ms_merge * 1e3, "extra_us": (ms_merge - ms_per_step) * 1e3,
+                                 "units_merging": len(merging), "similarity_gflop": flop / 1e9}
 
     if not args.no_breakdown and not args.full_budget and not args.no_full_cache_reference:
         result["full_cache_reference"] = full_cache_leg(hk, cfg, wl, torch, args, time_schedule,
