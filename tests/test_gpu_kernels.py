@@ -373,6 +373,41 @@ def test_attention_matches_oracle(dtype, d, Nk, lens, tol, kernel):
     hk.close()
 
 
+def test_cut_and_streamed_attention_launches_agree_with_whole_work_items():
+    """Random unit counts, cache lengths and query counts: the 128-query kernel with every cut the pair
+    model likes, and in its streamed form (equal runs of key blocks), against the same kernel on whole
+    work items.  The partial results of a cut work item are added up in float32, so the outputs agree to
+    a bf16 rounding of the output; each form runs twice on its context (the second launch meets the
+    counters and partial-result slots the first one left)."""
+    u = _u()
+    rng = np.random.default_rng(2024)
+    for case in range(8):
+        d = int(rng.choice([64, 128]))
+        H, B = int(rng.integers(1, 9)), int(rng.integers(1, 6))
+        U = H * B
+        Nk = int(rng.integers(1, 900))
+        lens = rng.integers(1, int(rng.choice([64, 700, 6000])) + 1, size=U).astype(np.int32)
+        off = np.concatenate([[0], np.cumsum((lens + 7) // 8 * 8)])[:-1].astype(np.int64)
+        rows = int(((lens + 7) // 8 * 8).sum())
+        K = (torch.randn((rows, d), device=u.DEV) * 1.5).to(torch.bfloat16)
+        V = torch.randn((rows, d), device=u.DEV).to(torch.bfloat16)
+        q = torch.randn((B, H, Nk, d), device=u.DEV).to(torch.bfloat16)
+        outs = {}
+        for kernel in ("tile128", "cut", "stream"):
+            hk = u.make_hack(heads=H, head_dim=d, dtype="bf16", max_units=U, max_cache_len=6000, max_queries=900,
+                             attention=kernel)
+            o = torch.full_like(q, 7.0)
+            for _ in range(2):
+                hk.attn(q, Cache(K, V, off, lens), float(1.0 / np.sqrt(d)), o)
+            torch.cuda.synchronize()
+            outs[kernel] = o.float().cpu().numpy()
+            hk.close()
+        for kernel in ("cut", "stream"):
+            assert np.isfinite(outs[kernel]).all(), (case, kernel)
+            err = float(np.abs(outs[kernel] - outs["tile128"]).max())
+            assert err < 2e-2, (case, kernel, d, U, Nk, int(lens.max()), err)
+
+
 def test_attention_rejects_empty_unit_and_bad_scale():
     u = _u()
     hk = u.make_hack(heads=1, head_dim=64, dtype="bf16", max_units=1, max_cache_len=64, max_queries=8)
