@@ -157,7 +157,7 @@ __global__ __launch_bounds__(kThreads, 4) void merge_nearest(
   }
   // One block against this lane's 16 kept rows: the block's largest value displaces the running best only if it
   // is strictly larger (an equal later row does not displace an earlier one), and among equal values of the block
-  // the lowest row wins.  Branch-free: a short tree of maxima, then the lowest row that attains the maximum.
+  // the lowest row wins.  A short tree of maxima, then the lowest row that attains the maximum.
   auto update = [&](const floatx16& sc, int blk, int nv, bool ragged, float& bst, int& ag) {
     const float* invs = &inv_ring[blk % kRing][w][0];
     float v[16];
@@ -175,13 +175,15 @@ __global__ __launch_bounds__(kThreads, 4) void merge_nearest(
 #pragma unroll
     for (int g4 = 0; g4 < 4; ++g4) m4[g4] = fmaxf(fmaxf(v[4 * g4], v[4 * g4 + 1]), fmaxf(v[4 * g4 + 2], v[4 * g4 + 3]));
     const float vmax = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
-    int first = 0;
-#pragma unroll
-    for (int q = 15; q >= 0; --q)                         // descending, so the lowest matching row is written last
-      first = (v[q] == vmax) ? 8 * (q >> 2) + 4 * half + (q & 3) : first;
     const bool moved = vmax > bst;
-    bst = moved ? vmax : bst;
-    ag = moved ? blk * 32 + first : ag;
+    if (__any(moved)) {                                   // the row is only looked for when some lane's best moved
+      int first = 0;
+#pragma unroll
+      for (int q = 15; q >= 0; --q)                       // descending, so the lowest matching row is written last
+        first = (v[q] == vmax) ? 8 * (q >> 2) + 4 * half + (q & 3) : first;
+      bst = moved ? vmax : bst;
+      ag = moved ? blk * 32 + first : ag;
+    }
   };
   auto scores = [&](int blk, floatx16& sc) {
     const __bf16* slot = &ring[blk % kRing][0];
@@ -203,11 +205,14 @@ __global__ __launch_bounds__(kThreads, 4) void merge_nearest(
     const bool two = blk + 1 < n_blocks;                    // wave-uniform
     scores(blk, s0);
     if (two) scores(blk + 1, s1);
+    // the ragged form (rows past the end masked) is a separate instance, taken by the last block only
     const int nv0 = min(32, b - blk * 32);
-    update(s0, blk, nv0, nv0 < 32, best[0], arg[0]);
+    if (nv0 == 32) update(s0, blk, 32, false, best[0], arg[0]);
+    else update(s0, blk, nv0, true, best[0], arg[0]);
     if (two) {
       const int nv1 = min(32, b - (blk + 1) * 32);
-      update(s1, blk + 1, nv1, nv1 < 32, best[0], arg[0]);
+      if (nv1 == 32) update(s1, blk + 1, 32, false, best[0], arg[0]);
+      else update(s1, blk + 1, nv1, true, best[0], arg[0]);
     }
   }
 #pragma unroll
