@@ -185,8 +185,9 @@ constexpr int kFixLimit = 511 << 22;
 constexpr int kMaxGroups = 64;                 // work-groups per unit the exchange supports (4 * 128 keys each)
 constexpr unsigned long long kEmpty = ~0ull;   // exchange slot not published yet (a NaN pattern no row sum can have)
 __device__ __forceinline__ int fix_from(double t_scaled) {  // t_scaled = t * 2^22
-  t_scaled = fmin(fmax(t_scaled, -511.0 * kFixOne), 511.0 * kFixOne);
-  return __double2int_rn(t_scaled);
+  // the conversion saturates at the ends of the int range, far outside the clamp, so clamping the integer gives
+  // what clamping the double first would (one three-operand median instead of two fp64 min / max)
+  return min(max(__double2int_rn(t_scaled), -kFixLimit), kFixLimit);
 }
 __device__ __forceinline__ double exp2_fix(int qv) {
   const int n = qv >> 22;
@@ -350,14 +351,12 @@ __global__ __launch_bounds__(kThreads, 2) void score_fused(
       // only ever acts on partial sums that are small next to the full dot product.
       double sd[16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) sd[r] = 0.0;
-#pragma unroll
       for (int kk = 0; kk < KK; ++kk) {
         const bf16x8 kf = *reinterpret_cast<const bf16x8*>(&Kt[k_off[kk]]);
         floatx16 c = {0};
         c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(qf[kk], kf, c, 0, 0, 0);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sd[r] += (double)c[r];
+        for (int r = 0; r < 16; ++r) sd[r] = (kk == 0) ? (double)c[r] : sd[r] + (double)c[r];   // 0.0 + x == x: same bits
       }
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
