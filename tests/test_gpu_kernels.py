@@ -377,8 +377,8 @@ def test_cut_and_streamed_attention_launches_agree_with_whole_work_items():
     """Random unit counts, cache lengths and query counts: the 128-query kernel with every cut the pair
     model likes, and in its streamed form (equal runs of key blocks), against the same kernel on whole
     work items.  The partial results of a cut work item are added up in float32, so the outputs agree to
-    a bf16 rounding of the output; each form runs twice on its context (the second launch meets the
-    counters and partial-result slots the first one left)."""
+    a bf16 rounding of the output; each form runs many times on its context (every launch meets the
+    counters and partial-result slots the one before it left)."""
     u = _u()
     rng = np.random.default_rng(2024)
     for case in range(8):
@@ -392,20 +392,33 @@ def test_cut_and_streamed_attention_launches_agree_with_whole_work_items():
         K = (torch.randn((rows, d), device=u.DEV) * 1.5).to(torch.bfloat16)
         V = torch.randn((rows, d), device=u.DEV).to(torch.bfloat16)
         q = torch.randn((B, H, Nk, d), device=u.DEV).to(torch.bfloat16)
+        # Many launches back to back, alternating between two sets of queries: a part that was read before its
+        # writer's stores had arrived would be the other query set's, far outside the tolerance.
+        q2 = torch.randn((B, H, Nk, d), device=u.DEV).to(torch.bfloat16)
         outs = {}
         for kernel in ("tile128", "cut", "stream"):
             hk = u.make_hack(heads=H, head_dim=d, dtype="bf16", max_units=U, max_cache_len=6000, max_queries=900,
                              attention=kernel)
-            o = torch.full_like(q, 7.0)
-            for _ in range(2):
+            o, o2 = torch.full_like(q, 7.0), torch.full_like(q, 7.0)
+            first = None
+            for it in range(1 if kernel == "tile128" else 24):
                 hk.attn(q, Cache(K, V, off, lens), float(1.0 / np.sqrt(d)), o)
+                hk.attn(q2, Cache(K, V, off, lens), float(1.0 / np.sqrt(d)), o2)
+                if first is None:
+                    first = (o.clone(), o2.clone())
+                else:      # the parts are added up in a fixed order: every launch gives the same bits
+                    assert torch.equal(o, first[0]) and torch.equal(o2, first[1]), (case, kernel, it)
+                o.fill_(7.0)
+                o2.fill_(7.0)
+            o, o2 = first
             torch.cuda.synchronize()
-            outs[kernel] = o.float().cpu().numpy()
+            outs[kernel] = (o.float().cpu().numpy(), o2.float().cpu().numpy())
             hk.close()
         for kernel in ("cut", "stream"):
-            assert np.isfinite(outs[kernel]).all(), (case, kernel)
-            err = float(np.abs(outs[kernel] - outs["tile128"]).max())
-            assert err < 2e-2, (case, kernel, d, U, Nk, int(lens.max()), err)
+            for which in (0, 1):
+                assert np.isfinite(outs[kernel][which]).all(), (case, kernel)
+                err = float(np.abs(outs[kernel][which] - outs["tile128"][which]).max())
+                assert err < 2e-2, (case, kernel, which, d, U, Nk, int(lens.max()), err)
 
 
 def test_attention_rejects_empty_unit_and_bad_scale():
