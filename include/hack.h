@@ -83,7 +83,10 @@ typedef struct {
 /* ---- life cycle ------------------------------------------------------- */
 
 /* Creates a context on cfg->device and allocates its workspace (importance,
- * kept indices, softmax partials, launch tables).  Returns HACK_EINVAL for an
+ * kept indices, softmax partials, launch tables; for bf16 contexts also the
+ * merge workspace and the partial-result slots of cut attention work items:
+ * 2 x resident work-groups x 128 x head_dim floats, 64 MiB at head_dim 128 on
+ * MI355X).  Returns HACK_EINVAL for an
  * unsupported head_dim/dtype/n_obs or non-positive sizes, HACK_EHIP if the
  * device cannot be used. */
 hack_status hack_create(hack_ctx** out, const hack_config* cfg);
@@ -253,7 +256,10 @@ hack_status hack_attn(hack_ctx* ctx, int32_t B, int32_t N_k, const void* q,
  * batch elements and N_k queries per unit (same attention equation, same
  * tolerances; reported so that measurements can be attributed to a kernel):
  *   0  work items of 128 queries that share every K/V block (large steps; fp32
- *      contexts always),
+ *      contexts always); in a bf16 launch with no more work items than the
+ *      device holds work-groups, a few work items may be served by two
+ *      work-groups each (half of the keys each, the partial results added up
+ *      in float32 in a fixed order) where that shortens the launch,
  *   1  work items of 32 queries whose four waves split the keys and merge their
  *      partial softmax results at the end (bf16, early scale steps: few
  *      queries); in hack_step this kernel also performs the append when no unit
